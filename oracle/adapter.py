@@ -1,0 +1,32 @@
+"""Adapter that lets the emulated-learner loop (synth.replay) drive the CPU oracle.
+TEST INFRASTRUCTURE, like everything under oracle/."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import (HARDSYNC, LR_AVG_STALENESS, LR_CONST, LR_PER_GRADIENT, LR_STATIC_N, SOFTSYNC, OraclePS)
+
+PROTOCOL = {"hardsync": HARDSYNC, "softsync": SOFTSYNC}
+LR_MODE = {"const": LR_CONST, "static_n": LR_STATIC_N, "avg_staleness": LR_AVG_STALENESS,
+           "per_gradient": LR_PER_GRADIENT}
+
+
+class OracleServer:
+    """Oracle over the elements `index` of a workload's parameter vector (default: all of
+    them).  The update is elementwise, so a subset of indices replays exactly what the
+    full vector would hold at those positions."""
+
+    def __init__(self, workload, index=None, precision=32):
+        self.w = workload
+        self.index = np.arange(workload.n_params, dtype=np.uint64) if index is None else np.asarray(index, np.uint64)
+        self.ps = OraclePS(workload.init_weights_at(self.index), workload.n_learners, workload.n_split,
+                           PROTOCOL[workload.protocol], LR_MODE[workload.lr_mode], workload.alpha0,
+                           workload.lr_scale, workload.momentum, workload.weight_decay, workload.c_override,
+                           precision=precision)
+
+    def push(self, learner, step, ts):
+        rc, res = self.ps.push(self.w.grad_at(learner, step, self.index), ts, learner)
+        return rc, int(res.staleness), int(res.applied)
+
+    def pull_ts(self):
+        return self.ps.ts
