@@ -1,0 +1,183 @@
+/*
+ * rudra_ps.h -- C ABI of the MI355X (gfx950) parameter-server update path of Rudra
+ * ("Model Accuracy and Runtime Tradeoff in Distributed Deep Learning: A Systematic
+ * Study", arXiv 1509.04210).
+ *
+ * One rudra_ps_t is one parameter server: it holds the fp32 weight vector theta
+ * (and the momentum velocity v) in HBM, receives pushGradient messages, and, when
+ * the protocol says so, runs sumGradients + applyUpdate as ONE fused HIP kernel
+ * that reads each pushed gradient once and touches each weight once.
+ *
+ * Conventions
+ *   - "device pointer": memory of the GPU named in rudra_ps_config_t.device,
+ *     accessible to kernels on rudra_ps_config_t.stream.  "host pointer": ordinary
+ *     process memory.  Every pointer argument says which it is.
+ *   - Every function returns RUDRA_OK (0) or a negative rudra_status code.  Nothing
+ *     aborts, throws or exits.  A rejected call leaves the server unchanged.
+ *   - Calls on one server are serialised by an internal mutex: the order of
+ *     rudra_ps_push_gradient calls IS the arrival order of the gradients, and it
+ *     fixes the order of the floating-point additions (Sec. 3.2 "Parameter Server":
+ *     the server handles incoming messages one by one).
+ *   - All device work is enqueued on the caller's stream; push never waits for the GPU.
+ */
+#ifndef RUDRA_PS_H
+#define RUDRA_PS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rudra_ps rudra_ps_t; /* opaque; created and destroyed by the library */
+
+/* Synchronisation protocol (Sec. 3.1). */
+enum rudra_protocol {
+  RUDRA_HARDSYNC = 0, /* one gradient from each of the lambda learners per step, Eq. 2; staleness 0 */
+  RUDRA_SOFTSYNC = 1  /* n-softsync: update after c = floor(lambda/n) gradients, Eq. 4; n = lambda is Async, Eq. 3 */
+};
+
+/* How the learning rate of an update is formed from alpha0 (Sec. 3.2 "Parameter Server", Sec. 5.1 Eq. 5). */
+enum rudra_lr_mode {
+  RUDRA_LR_CONST = 0,         /* alpha0 * lr_scale (hardsync: lr_scale = sqrt(lambda*mu/B)) */
+  RUDRA_LR_STATIC_N = 1,      /* alpha0 * lr_scale / n */
+  RUDRA_LR_AVG_STALENESS = 2, /* alpha0 * lr_scale / max(1, <sigma>), <sigma> of this update's vector clock */
+  RUDRA_LR_PER_GRADIENT = 3   /* Sec. 5.1 footnote: gradient l is scaled by 1/max(1, sigma_l) before it is
+                                 summed; the update uses alpha0 * lr_scale */
+};
+
+enum rudra_flags {
+  RUDRA_FLAG_STATS_NORMS = 1u,     /* every applyUpdate also reduces ||gbar||^2, ||theta||^2, ||theta||_inf, ||v||^2 */
+  RUDRA_FLAG_PUSH_ACCUMULATE = 2u, /* sum each gradient into a server-owned accumulator at push time (the literal
+                                      "receive and accumulate" of Sec. 2); the caller's buffer is free again as
+                                      soon as work it enqueues later on the stream runs.  Same bits as the default. */
+  RUDRA_FLAG_CONTROL_ONLY = 4u,    /* timestamps, staleness, clocks and rates only: no device memory, no kernels;
+                                      grad may be NULL; pulling weights is an error.  For host-side tests. */
+  RUDRA_FLAG_TIME_KERNELS = 8u     /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t */
+};
+
+enum rudra_status {
+  RUDRA_OK = 0,
+  RUDRA_EINVAL = -1,          /* null/unaligned pointer, n outside [1, lambda], P = 0, unknown learner, ... */
+  RUDRA_EFUTURE_TS = -2,      /* gradient timestamp newer than the weights' (Sec. 3.1 requires ts_j >= ts_i) */
+  RUDRA_EHARDSYNC_STALE = -3, /* hardsync gradient not computed from the current weights (staleness must be 0) */
+  RUDRA_EHARDSYNC_DUP = -4,   /* hardsync: this learner already contributed to the current step */
+  RUDRA_ENOMEM = -5,          /* host or device allocation failed */
+  RUDRA_EHIP = -6,            /* a HIP call failed; rudra_ps_stats_t.last_hip_error has the hipError_t */
+  RUDRA_ERANGE = -7,          /* requested update index not (or no longer) in the clock ring / buffer too small */
+  RUDRA_ESTATE = -8           /* call not available in this mode (e.g. weights in CONTROL_ONLY mode) */
+};
+
+typedef struct {
+  uint64_t n_params;     /* P, number of fp32 parameters (> 0) */
+  uint32_t n_learners;   /* lambda (> 0) */
+  uint32_t n_split;      /* n of n-softsync, 1..lambda; ignored under hardsync */
+  uint32_t c_override;   /* 0: c = lambda (hardsync) or floor(lambda/n) (softsync); else gradients per update */
+  int32_t protocol;      /* enum rudra_protocol */
+  int32_t lr_mode;       /* enum rudra_lr_mode */
+  float alpha0;          /* base learning rate */
+  float lr_scale;        /* caller-known factor, e.g. sqrt(lambda*mu/B); use 1 when none */
+  float momentum;        /* 0 = plain SGD; else v <- m v - alpha gbar, theta <- theta + v (Sec. 4.2: 0.9) */
+  float weight_decay;    /* L2 penalty: gbar <- gbar + wd*theta (Sec. 4.2: 5e-4 on ImageNet) */
+  int32_t device;        /* HIP device ordinal */
+  uint32_t flags;        /* OR of enum rudra_flags */
+  void* stream;          /* hipStream_t, borrowed from the caller (NULL = the device's null stream) */
+  uint32_t clock_ring;   /* closed vector clocks kept for rudra_ps_vector_clock (0 = 1024) */
+  /* launch shape of the fused kernel; 0 = library default.  Results do not depend on it, except the order in
+     which the optional norms are reduced. */
+  uint32_t launch_block;  /* threads per workgroup: 64..1024, multiple of 64 */
+  uint32_t launch_unroll; /* gradient loads issued together per lane: 1, 2, 4 or 8 */
+  uint32_t launch_vec;    /* float4 vectors per lane per tile: 1, 2 or 4 */
+  uint32_t launch_grid;   /* upper bound on workgroups (grid-stride beyond it); 0 = one tile per workgroup */
+} rudra_ps_config_t;
+
+typedef struct {
+  uint64_t staleness; /* sigma = (weight timestamp at arrival) - ts, Sec. 3.1 */
+  uint64_t ts_after;  /* weight timestamp after this message was handled */
+  uint32_t pending;   /* gradients now waiting for the next update */
+  int32_t applied;    /* 1 if this push completed a set of c gradients and applyUpdate was enqueued */
+  float lr_used;      /* learning rate of that update (0 when applied == 0) */
+} rudra_push_result_t;
+
+typedef struct {
+  uint64_t ts_cur;          /* current weight timestamp = number of updates so far */
+  uint64_t n_pushes;        /* accepted gradients */
+  uint64_t n_updates;
+  uint64_t n_rejected;
+  uint64_t sigma_sum;       /* over all accepted gradients */
+  uint64_t sigma_max;
+  uint64_t hist_len;        /* sigma_max + 1 once a gradient has arrived (see rudra_ps_staleness_hist) */
+  uint64_t bytes_absorbed;  /* n_pushes * 4 * P */
+  double sigma_mean;        /* sigma_sum / n_pushes */
+  double last_avg_staleness; /* <sigma> of the latest update, Sec. 3.1 Eq. 1 */
+  double theta_sq, theta_inf, v_sq, gbar_sq; /* state after / averaged gradient of the latest update; only with
+                                                RUDRA_FLAG_STATS_NORMS and n_updates > 0 (norms_valid = 1) */
+  double kernel_ms;         /* RUDRA_FLAG_TIME_KERNELS: summed device time of the applyUpdate launches ... */
+  uint64_t kernel_launches; /* ... and how many launches that covers */
+  uint32_t pending;         /* gradients received since the latest update */
+  uint32_t c;               /* gradients per update */
+  float last_lr;
+  int32_t norms_valid;
+  int32_t last_hip_error;   /* hipError_t of the latest failed HIP call, 0 if none */
+  uint32_t reserved;
+} rudra_ps_stats_t;
+
+/* Create a server.  init_weights: DEVICE pointer to P floats, copied (the caller keeps its buffer); in
+ * CONTROL_ONLY mode it is ignored and may be NULL.  theta, v and any scratch are allocated with hipMalloc and
+ * owned by the library until rudra_ps_destroy.  Timestamp starts at 0 (Sec. 3.1), v at 0.
+ * Errors: EINVAL (bad config / null), ENOMEM, EHIP. */
+int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, rudra_ps_t** out);
+
+/* Wait for the stream, free everything.  NULL is allowed. */
+int rudra_ps_destroy(rudra_ps_t* ps);
+
+/* pushGradient as the server receives it (Sec. 2, Sec. 3.2): one gradient of P floats plus the timestamp of the
+ * weights it was computed from.  Computes its staleness, appends ts to the open vector clock and, on the c-th
+ * gradient, enqueues sumGradients+applyUpdate (Eq. 2 / Eq. 4 with the rate of the configured mode) and advances
+ * the weight timestamp by one.
+ *   grad     DEVICE pointer, P contiguous floats, 16-byte aligned.  BORROWED: unless PUSH_ACCUMULATE is set the
+ *            buffer must stay allocated and unmodified until the update that consumes it has run; work enqueued
+ *            on the same stream after the push that returned applied = 1 is safe, as is anything after
+ *            rudra_ps_sync.
+ *   ts       timestamp the learner obtained from rudra_ps_pull_weights
+ *   learner  0..lambda-1, or -1 for anonymous (no duplicate check under hardsync)
+ *   out      HOST pointer, may be NULL
+ * Errors: EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, EHIP. */
+int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out);
+
+/* pullWeights (Sec. 2, Sec. 3.2 "Learner"): the weights and their timestamp.  dst: DEVICE pointer to P floats
+ * receiving a copy enqueued on the stream after all updates so far, or NULL for the timestamp inquiry a learner
+ * makes first to skip the transfer.  ts_out: HOST pointer, may be NULL. */
+int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out);
+
+/* Copy of the momentum velocity v (DEVICE pointer to P floats), enqueued on the stream. */
+int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst);
+
+/* Counters and staleness statistics the server records (Sec. 3.2: it records the vector clock of each update to
+ * track the average staleness).  out: HOST pointer.  Waits for the stream only if norms or kernel times are on. */
+int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out);
+
+/* Staleness histogram (the distribution shown with the lambda-softsync measurement, Sec. 5.1): out[s] = number of
+ * accepted gradients with staleness s.  out: HOST pointer to cap entries; n_out: entries that exist. Copies
+ * min(cap, n) entries; ERANGE if cap < n (n_out is still set). */
+int rudra_ps_staleness_hist(rudra_ps_t* ps, uint64_t* out, uint64_t cap, uint64_t* n_out);
+
+/* Vector clock of update `update_idx` (0-based: the update advancing timestamp update_idx -> update_idx+1): the c
+ * gradient timestamps in arrival order, its <sigma> (Eq. 1) and its learning rate.  HOST pointers; avg_sigma_out and
+ * lr_out may be NULL.  ERANGE if the update has not happened, has left the ring, or cap < c. */
+int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out, uint32_t cap, uint32_t* n_out,
+                          double* avg_sigma_out, float* lr_out);
+
+/* Learning-rate schedule hook (Sec. 4.2: alpha0 is divided by 10 after given epochs; epochs are the caller's). */
+int rudra_ps_set_lr(rudra_ps_t* ps, float alpha0);
+
+/* Wait until everything enqueued so far has run. */
+int rudra_ps_sync(rudra_ps_t* ps);
+
+/* Static description of a status code. */
+const char* rudra_ps_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RUDRA_PS_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of include/rudra_ps.h: argument marshalling only.
+
+Names follow the C ABI (rudra_ps_create -> ParameterServer(...), rudra_ps_push_gradient ->
+.push_gradient, ...).  Device buffers are passed as integer addresses (e.g. torch
+`tensor.data_ptr()`); the stream as the integer hipStream_t (torch `stream.cuda_stream`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "lib", "librudra_ps.so")
+
+HARDSYNC, SOFTSYNC = 0, 1
+LR_CONST, LR_STATIC_N, LR_AVG_STALENESS, LR_PER_GRADIENT = 0, 1, 2, 3
+FLAG_STATS_NORMS, FLAG_PUSH_ACCUMULATE, FLAG_CONTROL_ONLY, FLAG_TIME_KERNELS = 1, 2, 4, 8
+OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM, EHIP, ERANGE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8
+
+
+class Config(C.Structure):
+    _fields_ = [("n_params", C.c_uint64), ("n_learners", C.c_uint32), ("n_split", C.c_uint32),
+                ("c_override", C.c_uint32), ("protocol", C.c_int32), ("lr_mode", C.c_int32),
+                ("alpha0", C.c_float), ("lr_scale", C.c_float), ("momentum", C.c_float),
+                ("weight_decay", C.c_float), ("device", C.c_int32), ("flags", C.c_uint32),
+                ("stream", C.c_void_p), ("clock_ring", C.c_uint32), ("launch_block", C.c_uint32),
+                ("launch_unroll", C.c_uint32), ("launch_vec", C.c_uint32), ("launch_grid", C.c_uint32)]
+
+
+class PushResult(C.Structure):
+    _fields_ = [("staleness", C.c_uint64), ("ts_after", C.c_uint64), ("pending", C.c_uint32),
+                ("applied", C.c_int32), ("lr_used", C.c_float)]
+
+
+class Stats(C.Structure):
+    _fields_ = [("ts_cur", C.c_uint64), ("n_pushes", C.c_uint64), ("n_updates", C.c_uint64),
+                ("n_rejected", C.c_uint64), ("sigma_sum", C.c_uint64), ("sigma_max", C.c_uint64),
+                ("hist_len", C.c_uint64), ("bytes_absorbed", C.c_uint64), ("sigma_mean", C.c_double),
+                ("last_avg_staleness", C.c_double), ("theta_sq", C.c_double), ("theta_inf", C.c_double),
+                ("v_sq", C.c_double), ("gbar_sq", C.c_double), ("kernel_ms", C.c_double),
+                ("kernel_launches", C.c_uint64), ("pending", C.c_uint32), ("c", C.c_uint32),
+                ("last_lr", C.c_float), ("norms_valid", C.c_int32), ("last_hip_error", C.c_int32),
+                ("reserved", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded HIP library.  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+                               "There is no CPU fallback.")
+        L = C.CDLL(LIB_PATH)
+        vp, u64, u32, i32 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int32
+        sigs = {
+            "rudra_ps_create": [C.POINTER(Config), vp, C.POINTER(vp)],
+            "rudra_ps_destroy": [vp],
+            "rudra_ps_push_gradient": [vp, vp, u64, i32, C.POINTER(PushResult)],
+            "rudra_ps_pull_weights": [vp, vp, C.POINTER(u64)],
+            "rudra_ps_pull_velocity": [vp, vp],
+            "rudra_ps_stats": [vp, C.POINTER(Stats)],
+            "rudra_ps_staleness_hist": [vp, C.POINTER(u64), u64, C.POINTER(u64)],
+            "rudra_ps_vector_clock": [vp, u64, C.POINTER(u64), u32, C.POINTER(u32), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_float)],
+            "rudra_ps_set_lr": [vp, C.c_float],
+            "rudra_ps_sync": [vp],
+        }
+        for name, args in sigs.items():
+            fn = getattr(L, name)
+            fn.argtypes, fn.restype = args, C.c_int
+        L.rudra_ps_strerror.argtypes, L.rudra_ps_strerror.restype = [C.c_int], C.c_char_p
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().rudra_ps_strerror(status).decode()
+
+
+class RudraError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: {strerror(status)} ({status})")
+        self.status = status
+
+
+class ParameterServer:
+    """One rudra_ps_t.  Methods return the C status where a caller may want to see a rejection
+    (push_gradient) and raise RudraError otherwise."""
+
+    def __init__(self, n_params, n_learners, init_weights_ptr=0, n_split=1, protocol=SOFTSYNC,
+                 lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0, weight_decay=0.0,
+                 c_override=0, device=0, stream=0, flags=0, clock_ring=0, launch_block=0, launch_unroll=0,
+                 launch_vec=0, launch_grid=0):
+        self._L = lib()
+        self.cfg = Config(n_params, n_learners, n_split, c_override, protocol, lr_mode, alpha0, lr_scale, momentum,
+                          weight_decay, device, flags, stream or None, clock_ring, launch_block, launch_unroll,
+                          launch_vec, launch_grid)
+        h = C.c_void_p()
+        rc = self._L.rudra_ps_create(C.byref(self.cfg), init_weights_ptr or None, C.byref(h))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_create")
+        self._h = h
+        self.n_params = n_params
+        self._res = PushResult()
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            self._L.rudra_ps_destroy(self._h)
+            self._h = None
+
+    __del__ = destroy
+
+    def push_gradient(self, grad_ptr, ts, learner=-1):
+        """(status, PushResult).  The PushResult object is reused by the next call."""
+        rc = self._L.rudra_ps_push_gradient(self._h, grad_ptr or None, ts, learner, C.byref(self._res))
+        return rc, self._res
+
+    def pull_weights(self, dst_ptr=0):
+        """Timestamp of the weights; with dst_ptr also enqueues the copy of theta."""
+        ts = C.c_uint64()
+        rc = self._L.rudra_ps_pull_weights(self._h, dst_ptr or None, C.byref(ts))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_pull_weights")
+        return ts.value
+
+    def pull_velocity(self, dst_ptr):
+        rc = self._L.rudra_ps_pull_velocity(self._h, dst_ptr)
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_pull_velocity")
+
+    def stats(self) -> Stats:
+        st = Stats()
+        rc = self._L.rudra_ps_stats(self._h, C.byref(st))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_stats")
+        return st
+
+    def staleness_hist(self):
+        n = C.c_uint64()
+        self._L.rudra_ps_staleness_hist(self._h, None, 0, C.byref(n))
+        buf = (C.c_uint64 * max(1, n.value))()
+        rc = self._L.rudra_ps_staleness_hist(self._h, buf, n.value, C.byref(n))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_staleness_hist")
+        return list(buf[:n.value])
+
+    def vector_clock(self, update_idx):
+        """(timestamps, <sigma>, lr) of one update; raises RudraError(ERANGE) if it left the ring."""
+        c = self.stats().c
+        buf = (C.c_uint64 * c)()
+        n, avg, lr = C.c_uint32(), C.c_double(), C.c_float()
+        rc = self._L.rudra_ps_vector_clock(self._h, update_idx, buf, c, C.byref(n), C.byref(avg), C.byref(lr))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_vector_clock")
+        return list(buf[:n.value]), avg.value, lr.value
+
+    def set_lr(self, alpha0):
+        rc = self._L.rudra_ps_set_lr(self._h, alpha0)
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_set_lr")
+
+    def sync(self):
+        rc = self._L.rudra_ps_sync(self._h)
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_sync")

@@ -1,0 +1,260 @@
+// Fused sumGradients + applyUpdate kernels of the Rudra parameter server (gfx950 / CDNA4).
+//
+// One launch reads each of the c pushed gradients once, reads and writes theta (and the
+// momentum velocity v) once, and does all of Eq. 4 (average of c gradients) and Eq. 1c
+// (theta <- theta - alpha * gbar), plus the momentum and weight-penalty terms of Sec. 4.2, in
+// registers.  The path is a pure HBM stream: (c+5) flops per (4c+16) bytes, so there is no
+// MFMA and no LDS staging here; what matters is 128-bit coalesced access, many independent
+// loads in flight per lane, and a launch with far more workgroups than the 256 CUs.
+//
+// Arithmetic contract (must stay bit-compatible with a sequential binary32 evaluation):
+//   s    = w_1*g_1[k]; s = s + w_l*g_l[k]  for l = 2..c, in arrival order   (w_l only in the
+//          per-gradient-staleness mode, Sec. 5.1 footnote; otherwise no multiply at all)
+//   gbar = s * inv_c;            if wd != 0: gbar = gbar + wd*theta[k]
+//   momentum:  v[k] = m*v[k] - lr*gbar ; theta[k] = theta[k] + v[k]
+//   otherwise: theta[k] = theta[k] - lr*gbar
+// every operation rounded on its own: this file is compiled with -ffp-contract=off and the
+// pragma below, so no multiply-add is ever fused.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+namespace rudra {
+
+constexpr int kMaxFused = 64;  // gradient pointers one launch can take (kernarg: 64*8 + 64*4 bytes)
+constexpr int kNumNorms = 4;   // gbar^2, theta^2, v^2, max|theta|
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct GradSet {
+  const float* p[kMaxFused];
+  float w[kMaxFused];
+};
+
+struct UpdateArgs {
+  float* theta;
+  float* vel;
+  float* sum_out;    // sum kernel only: where the running sum goes (may alias p[0])
+  double* partials;  // STATS: kNumNorms doubles per workgroup
+  uint64_t n_params;
+  uint64_t ntiles;   // ceil((n_params/4) / (blockDim*V)), computed on the host
+  uint32_t c;        // gradients in this launch, 1..kMaxFused
+  float inv_c, lr, momentum, weight_decay;
+};
+
+// Gradients are read exactly once per update: mark the loads non-temporal so they do not
+// displace theta/v lines in L2 / Infinity Cache.
+__device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
+  return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
+}
+__device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
+
+// Sum of the c gradients at V vector positions, in arrival order.  Loads are issued U
+// gradients x V positions at a time before the first add that needs them, so each lane keeps
+// up to U*V independent 16-byte loads in flight.
+template <bool WEIGHTED, int N, int V>
+__device__ __forceinline__ void add_n(const GradSet& gs, uint32_t j, const uint64_t (&iv)[V], floatx4 (&s)[V]) {
+  floatx4 t[N][V];
+#pragma unroll
+  for (int u = 0; u < N; ++u)
+#pragma unroll
+    for (int v = 0; v < V; ++v) t[u][v] = load_grad4(gs.p[j + u], iv[v]);
+#pragma unroll
+  for (int u = 0; u < N; ++u)
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      if (WEIGHTED) t[u][v] = t[u][v] * gs.w[j + u];
+      s[v] = s[v] + t[u][v];
+    }
+}
+
+template <bool WEIGHTED, int U, int V>
+__device__ __forceinline__ void sum_gradients(const GradSet& gs, uint32_t c, const uint64_t (&iv)[V],
+                                              floatx4 (&s)[V]) {
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    s[v] = load_grad4(gs.p[0], iv[v]);
+    if (WEIGHTED) s[v] = s[v] * gs.w[0];
+  }
+  uint32_t j = 1;
+  for (; j + U <= c; j += U) add_n<WEIGHTED, U, V>(gs, j, iv, s);
+  if (U > 4 && (c - j) & 4u) { add_n<WEIGHTED, 4, V>(gs, j, iv, s); j += 4; }
+  if (U > 2 && (c - j) & 2u) { add_n<WEIGHTED, 2, V>(gs, j, iv, s); j += 2; }
+  if (U > 1 && (c - j) & 1u) { add_n<WEIGHTED, 1, V>(gs, j, iv, s); j += 1; }
+}
+
+template <bool WEIGHTED>
+__device__ __forceinline__ float sum_gradients_scalar(const GradSet& gs, uint32_t c, uint64_t k) {
+  float s = load_grad1(gs.p[0], k);
+  if (WEIGHTED) s = s * gs.w[0];
+  for (uint32_t j = 1; j < c; ++j) {
+    float t = load_grad1(gs.p[j], k);
+    if (WEIGHTED) t = t * gs.w[j];
+    s = s + t;
+  }
+  return s;
+}
+
+struct Norms {
+  float gbar_sq, theta_sq, v_sq, theta_inf;
+};
+
+// applyUpdate on one element.  The single place where the update rule is written.
+template <bool MOMENTUM, bool STATS>
+__device__ __forceinline__ void update_element(float s, float& th, float& v, const UpdateArgs& a, Norms& n) {
+  float gbar = s * a.inv_c;
+  if (a.weight_decay != 0.0f) {
+    float penalty = a.weight_decay * th;
+    gbar = gbar + penalty;
+  }
+  if (MOMENTUM) {
+    float keep = a.momentum * v;
+    float step = a.lr * gbar;
+    v = keep - step;
+    th = th + v;
+  } else {
+    float step = a.lr * gbar;
+    th = th - step;
+  }
+  if (STATS) {
+    n.gbar_sq += gbar * gbar;
+    n.theta_sq += th * th;
+    if (MOMENTUM) n.v_sq += v * v;
+    n.theta_inf = fmaxf(n.theta_inf, fabsf(th));
+  }
+}
+
+template <bool MOMENTUM, bool STATS>
+__device__ __forceinline__ void update_vec4(const floatx4& s, floatx4& th, floatx4& ve, const UpdateArgs& a, Norms& n) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float t = th[i], v = MOMENTUM ? ve[i] : 0.f;
+    update_element<MOMENTUM, STATS>(s[i], t, v, a, n);
+    th[i] = t;
+    if (MOMENTUM) ve[i] = v;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_down(x, off, 64));
+  return x;
+}
+
+// Norm partials: each lane's fp32 partial -> wavefront reduction (cross-lane shuffles) -> the
+// workgroup's waves combined in wave order by lane 0 in fp64 -> one slot per workgroup.  No
+// atomics: the host adds the slots in workgroup order, so the result is reproducible for a
+// given launch shape.
+__device__ __forceinline__ void block_reduce_norms(const Norms& n, double* partials) {
+  __shared__ float lds[16][kNumNorms];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = (blockDim.x + 63) >> 6;
+  float g = wave_sum(n.gbar_sq), t = wave_sum(n.theta_sq), v = wave_sum(n.v_sq), m = wave_max(n.theta_inf);
+  if (lane == 0) {
+    lds[wave][0] = g; lds[wave][1] = t; lds[wave][2] = v; lds[wave][3] = m;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double dg = 0.0, dt = 0.0, dv = 0.0, dm = 0.0;
+    for (int w = 0; w < nwaves; ++w) {
+      dg += (double)lds[w][0]; dt += (double)lds[w][1]; dv += (double)lds[w][2];
+      dm = fmax(dm, (double)lds[w][3]);
+    }
+    double* out = partials + (uint64_t)blockIdx.x * kNumNorms;
+    out[0] = dg; out[1] = dt; out[2] = dv; out[3] = dm;
+  }
+}
+
+// Tiling: the vector of n4 = P/4 float4 positions is cut into tiles of blockDim*V positions;
+// within a tile lane t handles positions t, t+blockDim, ... so every load instruction of a
+// wave covers 1 KiB contiguous and a workgroup walks blockDim*V*16 contiguous bytes of each of
+// the c+2 streams.  Workgroups take tiles blockIdx, blockIdx+gridDim, ... (grid-stride); the
+// host normally launches one workgroup per tile.  The last P%4 elements are done by the first
+// lanes of workgroup 0 with scalar accesses.
+template <bool MOMENTUM, bool WEIGHTED, bool STATS, int U, int V>
+__global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
+  const uint64_t n4 = a.n_params >> 2;
+  const uint64_t tile = (uint64_t)blockDim.x * V;
+  const uint64_t ntiles = a.ntiles;
+  floatx4* __restrict__ theta4 = reinterpret_cast<floatx4*>(a.theta);
+  floatx4* __restrict__ vel4 = reinterpret_cast<floatx4*>(a.vel);
+  Norms n = {0.f, 0.f, 0.f, 0.f};
+
+  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const uint64_t base = t * tile + threadIdx.x;
+    if (base + (uint64_t)(V - 1) * blockDim.x < n4) {  // all V positions of this lane in range
+      uint64_t iv[V];
+      floatx4 th[V], ve[V] = {}, s[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) iv[v] = base + (uint64_t)v * blockDim.x;
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        th[v] = theta4[iv[v]];
+        if (MOMENTUM) ve[v] = vel4[iv[v]];
+      }
+      sum_gradients<WEIGHTED, U, V>(gs, a.c, iv, s);
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        update_vec4<MOMENTUM, STATS>(s[v], th[v], ve[v], a, n);
+        theta4[iv[v]] = th[v];
+        if (MOMENTUM) vel4[iv[v]] = ve[v];
+      }
+    } else {
+      for (int v = 0; v < V; ++v) {
+        const uint64_t i1[1] = {base + (uint64_t)v * blockDim.x};
+        if (i1[0] >= n4) break;
+        floatx4 th = theta4[i1[0]], ve = {0.f, 0.f, 0.f, 0.f}, s[1];
+        if (MOMENTUM) ve = vel4[i1[0]];
+        sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
+        update_vec4<MOMENTUM, STATS>(s[0], th, ve, a, n);
+        theta4[i1[0]] = th;
+        if (MOMENTUM) vel4[i1[0]] = ve;
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+    const uint64_t k = (n4 << 2) + threadIdx.x;
+    if (k < a.n_params) {
+      float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
+      float th = a.theta[k], ve = MOMENTUM ? a.vel[k] : 0.f;
+      update_element<MOMENTUM, STATS>(s, th, ve, a, n);
+      a.theta[k] = th;
+      if (MOMENTUM) a.vel[k] = ve;
+    }
+  }
+  if (STATS) block_reduce_norms(n, a.partials);
+}
+
+// sumGradients alone: sum_out[k] = w_1*g_1[k] + ... in arrival order.  Used when a gradient is
+// accumulated at push time and to fold sets of more than kMaxFused gradients; sum_out may be
+// the same buffer as gs.p[0] (each position is read, then written, by one lane).
+template <bool WEIGHTED, int U, int V>
+__global__ void sum_gradients_kernel(const GradSet gs, const UpdateArgs a) {
+  const uint64_t n4 = a.n_params >> 2;
+  const uint64_t tile = (uint64_t)blockDim.x * V;
+  const uint64_t ntiles = a.ntiles;
+  floatx4* out4 = reinterpret_cast<floatx4*>(a.sum_out);
+  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const uint64_t base = t * tile + threadIdx.x;
+    for (int v = 0; v < V; ++v) {
+      const uint64_t i1[1] = {base + (uint64_t)v * blockDim.x};
+      if (i1[0] >= n4) break;
+      floatx4 s[1];
+      sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
+      out4[i1[0]] = s[0];
+    }
+  }
+  if (blockIdx.x == 0) {
+    const uint64_t k = (n4 << 2) + threadIdx.x;
+    if (k < a.n_params) a.sum_out[k] = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
+  }
+}
+
+}  // namespace rudra

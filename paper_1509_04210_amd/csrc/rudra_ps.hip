@@ -1,0 +1,576 @@
+// Host control plane and C ABI of the Rudra parameter-server update path (see include/rudra_ps.h).
+//
+// Everything per message is O(1) integer work on the host (timestamps, staleness, vector
+// clock, trigger: Sec. 3.1; learning rate: Sec. 3.2 / Sec. 5.1 Eq. 5); the only device work is
+// the fused kernel launch on the c-th gradient.  No data crosses the host-device boundary on
+// the push path and push never waits for the GPU.
+#include "../../include/rudra_ps.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "apply_update.hip.h"
+
+using rudra::GradSet;
+using rudra::kMaxFused;
+using rudra::kNumNorms;
+using rudra::UpdateArgs;
+
+namespace {
+
+constexpr uint32_t kDefaultBlock = 256;
+constexpr uint32_t kDefaultUnroll = 4;
+constexpr uint32_t kDefaultVec = 1;
+constexpr uint32_t kDefaultClockRing = 1024;
+constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
+
+struct Pending {
+  const float* ptr;
+  float weight;
+};
+
+}  // namespace
+
+struct rudra_ps {
+  rudra_ps_config_t cfg;
+  std::mutex mu;
+  hipStream_t stream = nullptr;
+  uint32_t c = 0;
+  bool control_only = false, accumulate = false, want_norms = false, time_kernels = false;
+  bool failed = false;
+  int last_hip_error = 0;
+
+  // device state (owned)
+  float* theta = nullptr;
+  float* vel = nullptr;
+  float* acc = nullptr;        // running sum: PUSH_ACCUMULATE, or folding more than kMaxFused gradients
+  double* partials = nullptr;  // kNumNorms doubles per workgroup of the apply launch
+  uint32_t partials_blocks = 0;
+
+  // launch shape
+  uint32_t block = kDefaultBlock, unroll = kDefaultUnroll, vec = kDefaultVec, grid_cap = 0;
+
+  // protocol state
+  uint64_t ts_cur = 0;
+  uint32_t count = 0;
+  uint64_t sigma_sum_open = 0;
+  std::vector<uint64_t> open_clock;
+  std::vector<Pending> open_grads;
+  std::vector<uint8_t> seen;
+
+  // closed clocks (ring over update index)
+  uint32_t ring = kDefaultClockRing;
+  std::vector<uint64_t> ring_ts;
+  std::vector<double> ring_avg;
+  std::vector<float> ring_lr;
+
+  // statistics
+  std::vector<uint64_t> hist;
+  uint64_t n_pushes = 0, n_updates = 0, n_rejected = 0, sigma_sum = 0, sigma_max = 0;
+  double last_avg = 0.0;
+  float last_lr = 0.f;
+  uint32_t last_apply_blocks = 0;
+
+  // kernel timing
+  std::vector<hipEvent_t> ev_start, ev_stop;
+  uint64_t timed_launches = 0, timed_resolved = 0;
+  double kernel_ms = 0.0;
+};
+
+namespace {
+
+int hip_fail(rudra_ps* ps, hipError_t e) {
+  ps->last_hip_error = (int)e;
+  ps->failed = true;
+  return RUDRA_EHIP;
+}
+
+#define RUDRA_HIP(ps, call)                       \
+  do {                                            \
+    hipError_t e_ = (call);                       \
+    if (e_ != hipSuccess) return hip_fail(ps, e_); \
+  } while (0)
+
+uint32_t gradients_per_update(const rudra_ps_config_t& cfg) {
+  if (cfg.c_override) return cfg.c_override;
+  if (cfg.protocol == RUDRA_HARDSYNC) return cfg.n_learners;
+  return cfg.n_learners / cfg.n_split;
+}
+
+struct LaunchShape {
+  uint32_t grid, block;
+  uint64_t ntiles;
+};
+
+LaunchShape shape_for(const rudra_ps* ps) {
+  const uint64_t n4 = ps->cfg.n_params >> 2;
+  const uint64_t tile = (uint64_t)ps->block * ps->vec;
+  uint64_t tiles = (n4 + tile - 1) / tile;
+  uint64_t grid = tiles ? tiles : 1;  // the scalar tail still needs workgroup 0
+  if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
+  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;  // grid-stride covers the rest
+  return {(uint32_t)grid, ps->block, tiles};
+}
+
+// ---- kernel dispatch: runtime (momentum, weighted, stats, unroll, vec) -> template instance ----
+template <bool MOM, bool W, bool ST, int U>
+void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  switch (vec) {
+    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+  }
+}
+template <bool MOM, bool W, bool ST>
+void launch_apply_u(uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  switch (unroll) {
+    case 1: launch_apply_v<MOM, W, ST, 1>(vec, s, st, gs, a); break;
+    case 2: launch_apply_v<MOM, W, ST, 2>(vec, s, st, gs, a); break;
+    case 4: launch_apply_v<MOM, W, ST, 4>(vec, s, st, gs, a); break;
+    default: launch_apply_v<MOM, W, ST, 8>(vec, s, st, gs, a); break;
+  }
+}
+void launch_apply(bool mom, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
+                  const GradSet& gs, const UpdateArgs& a) {
+  const int key = (mom ? 4 : 0) | (weighted ? 2 : 0) | (stats ? 1 : 0);
+  switch (key) {
+    case 0: launch_apply_u<false, false, false>(unroll, vec, s, st, gs, a); break;
+    case 1: launch_apply_u<false, false, true>(unroll, vec, s, st, gs, a); break;
+    case 2: launch_apply_u<false, true, false>(unroll, vec, s, st, gs, a); break;
+    case 3: launch_apply_u<false, true, true>(unroll, vec, s, st, gs, a); break;
+    case 4: launch_apply_u<true, false, false>(unroll, vec, s, st, gs, a); break;
+    case 5: launch_apply_u<true, false, true>(unroll, vec, s, st, gs, a); break;
+    case 6: launch_apply_u<true, true, false>(unroll, vec, s, st, gs, a); break;
+    default: launch_apply_u<true, true, true>(unroll, vec, s, st, gs, a); break;
+  }
+}
+void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  // the fold/accumulate path is not the measured one: a single shape (4 loads in flight)
+  if (weighted) {
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+  } else {
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+  }
+}
+
+UpdateArgs base_args(const rudra_ps* ps) {
+  UpdateArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.theta = ps->theta;
+  a.vel = ps->vel;
+  a.sum_out = ps->acc;
+  a.partials = ps->partials;
+  a.n_params = ps->cfg.n_params;
+  a.momentum = ps->cfg.momentum;
+  a.weight_decay = ps->cfg.weight_decay;
+  return a;
+}
+
+int ensure_acc(rudra_ps* ps) {
+  if (ps->acc) return RUDRA_OK;
+  hipError_t e = hipMalloc((void**)&ps->acc, ps->cfg.n_params * sizeof(float));
+  if (e == hipErrorOutOfMemory) { ps->last_hip_error = (int)e; return RUDRA_ENOMEM; }
+  if (e != hipSuccess) return hip_fail(ps, e);
+  return RUDRA_OK;
+}
+
+// acc <- sum of `n` entries of `g` (which may start with acc itself), arrival order kept.
+int enqueue_sum(rudra_ps* ps, const Pending* g, uint32_t n, bool weighted) {
+  GradSet gs;
+  std::memset(&gs, 0, sizeof(gs));
+  for (uint32_t j = 0; j < n; ++j) { gs.p[j] = g[j].ptr; gs.w[j] = g[j].weight; }
+  UpdateArgs a = base_args(ps);
+  a.c = n;
+  const LaunchShape s = shape_for(ps);
+  a.ntiles = s.ntiles;
+  launch_sum(weighted, s, ps->vec, ps->stream, gs, a);
+  RUDRA_HIP(ps, hipGetLastError());
+  return RUDRA_OK;
+}
+
+int resolve_timer(rudra_ps* ps, uint64_t launch_idx) {
+  const uint32_t slot = (uint32_t)(launch_idx % kTimerRing);
+  RUDRA_HIP(ps, hipEventSynchronize(ps->ev_stop[slot]));
+  float ms = 0.f;
+  RUDRA_HIP(ps, hipEventElapsedTime(&ms, ps->ev_start[slot], ps->ev_stop[slot]));
+  ps->kernel_ms += (double)ms;
+  ps->timed_resolved = launch_idx + 1;
+  return RUDRA_OK;
+}
+
+// sumGradients + applyUpdate for the c pending gradients (Eq. 2 / Eq. 4), one fused launch
+// when c <= kMaxFused.
+int enqueue_update(rudra_ps* ps, float lr) {
+  const bool weighted = ps->cfg.lr_mode == RUDRA_LR_PER_GRADIENT;
+  std::vector<Pending>& g = ps->open_grads;
+  size_t first = 0;
+  Pending head = {nullptr, 1.0f};
+  bool have_head = false;
+  // fold leading groups into acc until what is left fits one launch
+  while ((g.size() - first) + (have_head ? 1 : 0) > (size_t)kMaxFused) {
+    int rc = ensure_acc(ps);
+    if (rc != RUDRA_OK) return rc;
+    Pending group[kMaxFused];
+    uint32_t n = 0;
+    if (have_head) group[n++] = head;
+    while (n < (uint32_t)kMaxFused) group[n++] = g[first++];
+    rc = enqueue_sum(ps, group, n, weighted);
+    if (rc != RUDRA_OK) return rc;
+    head = {ps->acc, 1.0f};
+    have_head = true;
+  }
+  GradSet gs;
+  std::memset(&gs, 0, sizeof(gs));
+  uint32_t n = 0;
+  if (have_head) { gs.p[n] = head.ptr; gs.w[n] = head.weight; ++n; }
+  for (; first < g.size(); ++first, ++n) { gs.p[n] = g[first].ptr; gs.w[n] = g[first].weight; }
+
+  UpdateArgs a = base_args(ps);
+  a.c = n;
+  a.inv_c = 1.0f / (float)ps->c;  // Eq. 4: the mean is over all c gradients of the update
+  a.lr = lr;
+  const LaunchShape s = shape_for(ps);
+  a.ntiles = s.ntiles;
+  uint32_t slot = 0;
+  if (ps->time_kernels) {
+    if (ps->timed_launches - ps->timed_resolved >= kTimerRing) {
+      int rc = resolve_timer(ps, ps->timed_resolved);
+      if (rc != RUDRA_OK) return rc;
+    }
+    slot = (uint32_t)(ps->timed_launches % kTimerRing);
+    RUDRA_HIP(ps, hipEventRecord(ps->ev_start[slot], ps->stream));
+  }
+  launch_apply(ps->cfg.momentum != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
+  RUDRA_HIP(ps, hipGetLastError());
+  if (ps->time_kernels) {
+    RUDRA_HIP(ps, hipEventRecord(ps->ev_stop[slot], ps->stream));
+    ps->timed_launches += 1;
+  }
+  ps->last_apply_blocks = s.grid;
+  return RUDRA_OK;
+}
+
+void count_staleness(rudra_ps* ps, uint64_t sigma) {
+  if (sigma >= ps->hist.size()) ps->hist.resize(sigma + 1, 0);
+  ps->hist[sigma] += 1;
+  ps->sigma_sum += sigma;
+  ps->sigma_max = std::max(ps->sigma_max, sigma);
+}
+
+int validate_config(const rudra_ps_config_t* c) {
+  if (c->n_params == 0 || c->n_learners == 0) return RUDRA_EINVAL;
+  if (c->protocol != RUDRA_HARDSYNC && c->protocol != RUDRA_SOFTSYNC) return RUDRA_EINVAL;
+  if (c->lr_mode < RUDRA_LR_CONST || c->lr_mode > RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;
+  if (c->protocol == RUDRA_SOFTSYNC && (c->n_split < 1 || c->n_split > c->n_learners)) return RUDRA_EINVAL;
+  if (gradients_per_update(*c) == 0) return RUDRA_EINVAL;
+  if (c->launch_block && (c->launch_block < 64 || c->launch_block > 1024 || c->launch_block % 64)) return RUDRA_EINVAL;
+  if (c->launch_unroll && c->launch_unroll != 1 && c->launch_unroll != 2 && c->launch_unroll != 4 && c->launch_unroll != 8)
+    return RUDRA_EINVAL;
+  if (c->launch_vec && c->launch_vec != 1 && c->launch_vec != 2 && c->launch_vec != 4) return RUDRA_EINVAL;
+  if ((c->launch_unroll ? c->launch_unroll : kDefaultUnroll) * (c->launch_vec ? c->launch_vec : kDefaultVec) > 8)
+    return RUDRA_EINVAL;  // more 16-byte loads per lane than the register file holds without spilling
+  if (c->flags & ~(uint32_t)(RUDRA_FLAG_STATS_NORMS | RUDRA_FLAG_PUSH_ACCUMULATE | RUDRA_FLAG_CONTROL_ONLY | RUDRA_FLAG_TIME_KERNELS))
+    return RUDRA_EINVAL;
+  if (!(c->alpha0 == c->alpha0) || !(c->lr_scale == c->lr_scale) || !(c->momentum == c->momentum) ||
+      !(c->weight_decay == c->weight_decay))
+    return RUDRA_EINVAL;  // NaN
+  return RUDRA_OK;
+}
+
+void release(rudra_ps* ps) {
+  if (!ps->control_only) {
+    (void)hipSetDevice(ps->cfg.device);
+    (void)hipStreamSynchronize(ps->stream);
+    for (hipEvent_t e : ps->ev_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ps->ev_stop) (void)hipEventDestroy(e);
+    if (ps->theta) (void)hipFree(ps->theta);
+    if (ps->vel) (void)hipFree(ps->vel);
+    if (ps->acc) (void)hipFree(ps->acc);
+    if (ps->partials) (void)hipFree(ps->partials);
+  }
+  delete ps;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, rudra_ps_t** out) {
+  if (!config || !out) return RUDRA_EINVAL;
+  *out = nullptr;
+  int rc = validate_config(config);
+  if (rc != RUDRA_OK) return rc;
+  const bool control_only = (config->flags & RUDRA_FLAG_CONTROL_ONLY) != 0;
+  if (!control_only && !init_weights) return RUDRA_EINVAL;
+  if (!control_only && (reinterpret_cast<uintptr_t>(init_weights) & 3u)) return RUDRA_EINVAL;
+
+  rudra_ps* ps = new (std::nothrow) rudra_ps();
+  if (!ps) return RUDRA_ENOMEM;
+  ps->cfg = *config;
+  ps->control_only = control_only;
+  ps->accumulate = (config->flags & RUDRA_FLAG_PUSH_ACCUMULATE) != 0;
+  ps->want_norms = (config->flags & RUDRA_FLAG_STATS_NORMS) != 0 && !control_only;
+  ps->time_kernels = (config->flags & RUDRA_FLAG_TIME_KERNELS) != 0 && !control_only;
+  ps->stream = (hipStream_t)config->stream;
+  ps->c = gradients_per_update(*config);
+  if (config->launch_block) ps->block = config->launch_block;
+  if (config->launch_unroll) ps->unroll = config->launch_unroll;
+  if (config->launch_vec) ps->vec = config->launch_vec;
+  ps->grid_cap = config->launch_grid;
+  ps->ring = config->clock_ring ? config->clock_ring : kDefaultClockRing;
+  try {
+    ps->open_clock.assign(ps->c, 0);
+    ps->open_grads.reserve(ps->c);
+    ps->seen.assign(config->n_learners, 0);
+    ps->ring_ts.assign((size_t)ps->ring * ps->c, 0);
+    ps->ring_avg.assign(ps->ring, 0.0);
+    ps->ring_lr.assign(ps->ring, 0.f);
+    ps->hist.reserve(64);
+  } catch (const std::bad_alloc&) {
+    delete ps;
+    return RUDRA_ENOMEM;
+  }
+  if (!control_only) {
+    const size_t bytes = config->n_params * sizeof(float);
+    hipError_t e = hipSetDevice(config->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&ps->theta, bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&ps->vel, bytes);
+    if (e == hipSuccess && ps->accumulate) e = hipMalloc((void**)&ps->acc, bytes);
+    if (e == hipSuccess) e = hipMemcpyAsync(ps->theta, init_weights, bytes, hipMemcpyDeviceToDevice, ps->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(ps->vel, 0, bytes, ps->stream);
+    if (e == hipSuccess && ps->want_norms) {
+      ps->partials_blocks = shape_for(ps).grid;
+      e = hipMalloc((void**)&ps->partials, (size_t)ps->partials_blocks * kNumNorms * sizeof(double));
+    }
+    if (e == hipSuccess && ps->time_kernels) {
+      ps->ev_start.resize(kTimerRing);
+      ps->ev_stop.resize(kTimerRing);
+      for (uint32_t i = 0; i < kTimerRing && e == hipSuccess; ++i) {
+        e = hipEventCreate(&ps->ev_start[i]);
+        if (e == hipSuccess) e = hipEventCreate(&ps->ev_stop[i]);
+      }
+    }
+    if (e != hipSuccess) {
+      release(ps);
+      return e == hipErrorOutOfMemory ? RUDRA_ENOMEM : RUDRA_EHIP;
+    }
+  }
+  *out = ps;
+  return RUDRA_OK;
+}
+
+int rudra_ps_destroy(rudra_ps_t* ps) {
+  if (!ps) return RUDRA_OK;
+  release(ps);
+  return RUDRA_OK;
+}
+
+int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->failed) return RUDRA_EHIP;
+  const rudra_ps_config_t& cfg = ps->cfg;
+  // ---- validation: a rejected message changes nothing but the rejection counter ----
+  if (!ps->control_only && (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u))) { ps->n_rejected++; return RUDRA_EINVAL; }
+  if (learner < -1 || learner >= (int32_t)cfg.n_learners) { ps->n_rejected++; return RUDRA_EINVAL; }
+  if (ts > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
+  if (cfg.protocol == RUDRA_HARDSYNC) {
+    if (ts != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }
+    if (learner >= 0 && ps->seen[learner]) { ps->n_rejected++; return RUDRA_EHARDSYNC_DUP; }
+  }
+  // ---- staleness and vector clock (Sec. 3.1) ----
+  const uint64_t sigma = ps->ts_cur - ts;
+  float weight = 1.0f;
+  if (cfg.lr_mode == RUDRA_LR_PER_GRADIENT) weight = (float)(1.0 / (sigma > 1 ? (double)sigma : 1.0));
+
+  if (!ps->control_only) {
+    if (hipSetDevice(cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
+    if (ps->accumulate) {  // sumGradients at arrival: acc = w*g, or acc = acc + w*g
+      const bool weighted = cfg.lr_mode == RUDRA_LR_PER_GRADIENT;
+      Pending two[2] = {{ps->acc, 1.0f}, {grad, weight}};
+      int rc = (ps->count == 0) ? enqueue_sum(ps, two + 1, 1, weighted) : enqueue_sum(ps, two, 2, weighted);
+      if (rc != RUDRA_OK) return rc;
+    }
+  }
+  count_staleness(ps, sigma);
+  ps->open_clock[ps->count] = ts;
+  if (!ps->accumulate) ps->open_grads.push_back({grad, weight});
+  ps->count += 1;
+  ps->sigma_sum_open += sigma;
+  ps->n_pushes += 1;
+  if (learner >= 0 && cfg.protocol == RUDRA_HARDSYNC) ps->seen[learner] = 1;
+
+  int applied = 0;
+  float lr_used = 0.f;
+  if (ps->count == ps->c) {
+    // <sigma> of this update: mean over its clock of (ts_cur - ts_k) = (i-1) - mean(i_k), Eq. 1
+    const double avg_sigma = (double)ps->sigma_sum_open / (double)ps->c;
+    double lr = (double)cfg.alpha0 * (double)cfg.lr_scale;
+    if (cfg.lr_mode == RUDRA_LR_STATIC_N) lr = lr / (double)cfg.n_split;
+    else if (cfg.lr_mode == RUDRA_LR_AVG_STALENESS) lr = lr / (avg_sigma > 1.0 ? avg_sigma : 1.0);
+    lr_used = (float)lr;
+    if (!ps->control_only) {
+      if (ps->accumulate) {
+        ps->open_grads.clear();
+        ps->open_grads.push_back({ps->acc, 1.0f});
+      }
+      int rc = enqueue_update(ps, lr_used);
+      if (rc != RUDRA_OK) { ps->failed = true; return rc; }
+    }
+    const size_t slot = (size_t)(ps->n_updates % ps->ring);
+    std::copy(ps->open_clock.begin(), ps->open_clock.end(), ps->ring_ts.begin() + slot * ps->c);
+    ps->ring_avg[slot] = avg_sigma;
+    ps->ring_lr[slot] = lr_used;
+    ps->last_avg = avg_sigma;
+    ps->last_lr = lr_used;
+    ps->n_updates += 1;
+    ps->ts_cur += 1;  // each weight update increments the timestamp
+    ps->count = 0;
+    ps->sigma_sum_open = 0;
+    ps->open_grads.clear();
+    std::fill(ps->seen.begin(), ps->seen.end(), 0);
+    applied = 1;
+  }
+  if (out) {
+    out->staleness = sigma;
+    out->ts_after = ps->ts_cur;
+    out->pending = ps->count;
+    out->applied = applied;
+    out->lr_used = lr_used;
+  }
+  return RUDRA_OK;
+}
+
+int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (dst) {
+    if (ps->control_only) return RUDRA_ESTATE;
+    if (ps->failed) return RUDRA_EHIP;
+    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->theta, ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+  }
+  if (ts_out) *ts_out = ps->ts_cur;
+  return RUDRA_OK;
+}
+
+int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst) {
+  if (!ps || !dst) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+  RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->vel, ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+  return RUDRA_OK;
+}
+
+int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
+  if (!ps || !out) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  std::memset(out, 0, sizeof(*out));
+  out->ts_cur = ps->ts_cur;
+  out->n_pushes = ps->n_pushes;
+  out->n_updates = ps->n_updates;
+  out->n_rejected = ps->n_rejected;
+  out->sigma_sum = ps->sigma_sum;
+  out->sigma_max = ps->sigma_max;
+  out->hist_len = ps->hist.size();
+  out->bytes_absorbed = ps->n_pushes * 4ull * ps->cfg.n_params;
+  out->sigma_mean = ps->n_pushes ? (double)ps->sigma_sum / (double)ps->n_pushes : 0.0;
+  out->last_avg_staleness = ps->last_avg;
+  out->pending = ps->count;
+  out->c = ps->c;
+  out->last_lr = ps->last_lr;
+  out->last_hip_error = ps->last_hip_error;
+  if (ps->failed) return RUDRA_EHIP;
+  if (ps->time_kernels) {
+    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    while (ps->timed_resolved < ps->timed_launches) {
+      int rc = resolve_timer(ps, ps->timed_resolved);
+      if (rc != RUDRA_OK) return rc;
+    }
+    out->kernel_ms = ps->kernel_ms;
+    out->kernel_launches = ps->timed_resolved;
+  }
+  if (ps->want_norms && ps->n_updates > 0 && ps->partials) {
+    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    std::vector<double> host((size_t)ps->last_apply_blocks * kNumNorms);
+    RUDRA_HIP(ps, hipMemcpyAsync(host.data(), ps->partials, host.size() * sizeof(double), hipMemcpyDeviceToHost, ps->stream));
+    RUDRA_HIP(ps, hipStreamSynchronize(ps->stream));
+    double g = 0.0, t = 0.0, v = 0.0, m = 0.0;
+    for (uint32_t b = 0; b < ps->last_apply_blocks; ++b) {  // workgroup order: reproducible
+      g += host[(size_t)b * kNumNorms + 0];
+      t += host[(size_t)b * kNumNorms + 1];
+      v += host[(size_t)b * kNumNorms + 2];
+      m = std::max(m, host[(size_t)b * kNumNorms + 3]);
+    }
+    out->gbar_sq = g; out->theta_sq = t; out->v_sq = v; out->theta_inf = m;
+    out->norms_valid = 1;
+  }
+  return RUDRA_OK;
+}
+
+int rudra_ps_staleness_hist(rudra_ps_t* ps, uint64_t* out, uint64_t cap, uint64_t* n_out) {
+  if (!ps || (!out && cap)) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  const uint64_t n = ps->hist.size();
+  if (n_out) *n_out = n;
+  const uint64_t k = std::min(n, cap);
+  if (k) std::memcpy(out, ps->hist.data(), k * sizeof(uint64_t));
+  return cap < n ? RUDRA_ERANGE : RUDRA_OK;
+}
+
+int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out, uint32_t cap, uint32_t* n_out,
+                          double* avg_sigma_out, float* lr_out) {
+  if (!ps || !ts_out) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (n_out) *n_out = ps->c;
+  if (update_idx >= ps->n_updates || ps->n_updates - update_idx > ps->ring || cap < ps->c) return RUDRA_ERANGE;
+  const size_t slot = (size_t)(update_idx % ps->ring);
+  std::memcpy(ts_out, ps->ring_ts.data() + slot * ps->c, ps->c * sizeof(uint64_t));
+  if (avg_sigma_out) *avg_sigma_out = ps->ring_avg[slot];
+  if (lr_out) *lr_out = ps->ring_lr[slot];
+  return RUDRA_OK;
+}
+
+int rudra_ps_set_lr(rudra_ps_t* ps, float alpha0) {
+  if (!ps || !(alpha0 == alpha0)) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  ps->cfg.alpha0 = alpha0;
+  return RUDRA_OK;
+}
+
+int rudra_ps_sync(rudra_ps_t* ps) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_OK;
+  RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+  RUDRA_HIP(ps, hipStreamSynchronize(ps->stream));
+  return RUDRA_OK;
+}
+
+const char* rudra_ps_strerror(int status) {
+  switch (status) {
+    case RUDRA_OK: return "ok";
+    case RUDRA_EINVAL: return "invalid argument";
+    case RUDRA_EFUTURE_TS: return "gradient timestamp is newer than the weight timestamp";
+    case RUDRA_EHARDSYNC_STALE: return "hardsync gradient was not computed from the current weights";
+    case RUDRA_EHARDSYNC_DUP: return "hardsync: learner already contributed to this step";
+    case RUDRA_ENOMEM: return "out of memory";
+    case RUDRA_EHIP: return "HIP call failed";
+    case RUDRA_ERANGE: return "index out of range or buffer too small";
+    case RUDRA_ESTATE: return "call not available in this mode";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

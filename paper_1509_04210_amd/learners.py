@@ -1,0 +1,84 @@
+"""Emulated learners feeding one ParameterServer on one GPU.
+
+Harness used by the GPU tests, smoke() and bench.py: torch supplies device memory and the
+stream, synth supplies the seeded gradients (generated on the device) and the arrival trace,
+and every step of the update path itself runs inside the HIP library.
+"""
+from __future__ import annotations
+
+import torch
+
+from synth import gradgen
+
+from . import binding as B
+
+PROTOCOL = {"hardsync": B.HARDSYNC, "softsync": B.SOFTSYNC}
+LR_MODE = {"const": B.LR_CONST, "static_n": B.LR_STATIC_N, "avg_staleness": B.LR_AVG_STALENESS,
+           "per_gradient": B.LR_PER_GRADIENT}
+
+
+class HipServer:
+    """A workload's parameter server on `device`, plus a ring of gradient buffers.
+
+    push(learner, step, ts) materialises that learner's gradient into the next ring buffer (generator kernel
+    on the server's stream) and pushes it.  With `pregenerated` > 0 the ring is filled once with that many
+    distinct gradients and pushes cycle through it without generating (throughput runs).
+    The ring holds at least c+1 buffers, so a buffer is only rewritten after the update that
+    consumed it was enqueued on the same stream.
+    """
+
+    def __init__(self, workload, flags=0, device=0, ring=None, pregenerated=0, **launch):
+        self.w = workload
+        self.dev = torch.device("cuda", device)
+        self.stream = torch.cuda.Stream(device=self.dev)
+        P = workload.n_params
+        n_ring = max(ring or 0, pregenerated, workload.c + 1)
+        self.ring = [torch.empty(P, dtype=torch.float32, device=self.dev) for _ in range(n_ring)]
+        init = torch.empty(P, dtype=torch.float32, device=self.dev)
+        torch.cuda.synchronize(self.dev)
+        self.sh = self.stream.cuda_stream
+        gradgen.fill_device(init.data_ptr(), P, workload.init_key(), workload.init_std, stream=self.sh)
+        self.ps = B.ParameterServer(P, workload.n_learners, init.data_ptr(), workload.n_split,
+                                    PROTOCOL[workload.protocol], LR_MODE[workload.lr_mode], workload.alpha0,
+                                    workload.lr_scale, workload.momentum, workload.weight_decay,
+                                    workload.c_override, device, self.sh, flags, **launch)
+        self.pregenerated = pregenerated
+        for i in range(pregenerated):
+            self._fill(self.ring[i], i % workload.n_learners, i // workload.n_learners)
+        self.ps.sync()
+        del init
+        self._next = 0
+
+    def _fill(self, buf, learner, step):
+        w = self.w
+        gradgen.fill_device(buf.data_ptr(), w.n_params, w.grad_key(learner, step), w.grad_std, w.tail_per,
+                            w.tail_factor, stream=self.sh)
+
+    def push(self, learner, step, ts):
+        buf = self.ring[self._next]
+        self._next = (self._next + 1) % (self.pregenerated or len(self.ring))
+        if not self.pregenerated:
+            self._fill(buf, learner, step)
+        rc, res = self.ps.push_gradient(buf.data_ptr(), ts, learner)
+        return rc, res.staleness, res.applied
+
+    def pull_ts(self):
+        return self.ps.pull_weights(0)
+
+    def weights(self):
+        out = torch.empty(self.w.n_params, dtype=torch.float32, device=self.dev)
+        torch.cuda.synchronize(self.dev)
+        self.ps.pull_weights(out.data_ptr())
+        self.ps.sync()
+        return out
+
+    def velocity(self):
+        out = torch.empty(self.w.n_params, dtype=torch.float32, device=self.dev)
+        torch.cuda.synchronize(self.dev)
+        self.ps.pull_velocity(out.data_ptr())
+        self.ps.sync()
+        return out
+
+    def close(self):
+        self.ps.destroy()
+        self.ring = []

@@ -1,0 +1,159 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and its control plane (timestamps, staleness, clocks, rates, rejections; RUDRA_FLAG_CONTROL_ONLY:
+no device work at all) agrees bit for bit with the CPU oracle on the workloads' arrival traces."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1509_04210_amd as R
+from oracle import OraclePS
+from paper_1509_04210_amd import binding as B
+from paper_1509_04210_amd.learners import LR_MODE, PROTOCOL
+from synth import configs, replay
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "rudra_ps.h")).read()
+    declared = set(re.findall(r"\b(rudra_ps_[a-z_]+)\s*\(", header))
+    assert {"rudra_ps_create", "rudra_ps_push_gradient", "rudra_ps_pull_weights", "rudra_ps_stats"} <= declared
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in include/rudra_ps.h but not exported"
+    assert len(declared) == 11
+
+
+def test_struct_layouts_match_the_header():
+    """Field order of the ctypes mirrors == field order in the header (a transposed field would shift everything)."""
+    header = open(os.path.join(ROOT, "include", "rudra_ps.h")).read()
+
+    def fields(struct_name):
+        body = re.search(r"typedef struct \{([^}]*)\} " + struct_name + ";", header).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        names = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            names += [n.strip().lstrip("*").strip() for n in decl.split(None, 1)[1].split(",")]
+        return names
+
+    assert fields("rudra_ps_config_t") == [f[0] for f in B.Config._fields_]
+    assert fields("rudra_push_result_t") == [f[0] for f in B.PushResult._fields_]
+    assert fields("rudra_ps_stats_t") == [f[0] for f in B.Stats._fields_]
+
+
+def test_strerror_and_null_arguments():
+    assert R.strerror(0) == "ok"
+    assert "newer" in R.strerror(B.EFUTURE_TS)
+    L = R.lib()
+    assert L.rudra_ps_create(None, None, None) == B.EINVAL
+    assert L.rudra_ps_push_gradient(None, None, 0, 0, None) == B.EINVAL
+    assert L.rudra_ps_destroy(None) == B.OK
+    for bad in (dict(n_params=0, n_learners=1), dict(n_params=1, n_learners=0), dict(n_params=1, n_learners=3, n_split=4),
+                dict(n_params=1, n_learners=3, n_split=0), dict(n_params=1, n_learners=3, launch_block=100),
+                dict(n_params=1, n_learners=3, launch_unroll=3), dict(n_params=1, n_learners=3, launch_unroll=8, launch_vec=4),
+                dict(n_params=1, n_learners=3, flags=1 << 20), dict(n_params=1, n_learners=3, alpha0=float("nan"))):
+        with pytest.raises(R.RudraError) as e:
+            R.ParameterServer(flags=bad.pop("flags", B.FLAG_CONTROL_ONLY), **bad)
+        assert e.value.status == B.EINVAL
+
+
+def test_rejections_mirror_the_oracle():
+    ps = R.ParameterServer(4, 3, protocol=B.HARDSYNC, lr_mode=B.LR_CONST, alpha0=0.5, flags=B.FLAG_CONTROL_ONLY)
+    ora = OraclePS(np.zeros(4, np.float32), 3, 1, oracle.HARDSYNC, oracle.LR_CONST, alpha0=0.5)
+    g = np.ones(4, np.float32)
+    script = [(1, 0), (0, 3), (0, -2), (0, 0), (0, 0), (0, 1), (0, 2), (0, 0), (1, 0), (1, 1), (2, 1), (1, 2)]
+    for ts, learner in script:
+        rc_h, r = ps.push_gradient(0, ts, learner)
+        rc_o, ro = ora.push(g, ts, learner)
+        assert rc_h == rc_o, (ts, learner)
+        if rc_h == 0:
+            assert (r.staleness, r.ts_after, r.pending, r.applied, r.lr_used) == \
+                   (ro.staleness, ro.ts_after, ro.pending, ro.applied, ro.lr_used)
+    st = ps.stats()
+    assert (st.n_pushes, st.n_updates, st.n_rejected, st.pending) == (ora.n_pushes, ora.n_updates, ora.n_rejected, ora.pending)
+    assert st.n_rejected == 6 and st.ts_cur == 2
+    with pytest.raises(R.RudraError) as e:      # no weights exist in control-only mode
+        ps.pull_weights(0x1000)
+    assert e.value.status == B.ESTATE
+
+
+class _Control:
+    def __init__(self, w, **kw):
+        self.ps = R.ParameterServer(w.n_params, w.n_learners, 0, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode],
+                                    w.alpha0, w.lr_scale, w.momentum, w.weight_decay, w.c_override,
+                                    flags=B.FLAG_CONTROL_ONLY, **kw)
+
+    def push(self, l, s, ts):
+        rc, r = self.ps.push_gradient(0, ts, l)
+        return rc, r.staleness, r.applied
+
+    def pull_ts(self):
+        return self.ps.pull_weights(0)
+
+
+class _OracleControl:
+    """The oracle on a one-element vector: its protocol side does not depend on P."""
+
+    def __init__(self, w):
+        self.ps = OraclePS(np.zeros(1, np.float32), w.n_learners, w.n_split, oracle.HARDSYNC if w.protocol == "hardsync" else oracle.SOFTSYNC,
+                           {"const": 0, "static_n": 1, "avg_staleness": 2, "per_gradient": 3}[w.lr_mode], w.alpha0,
+                           w.lr_scale, w.momentum, w.weight_decay, w.c_override)
+        self.g = np.zeros(1, np.float32)
+
+    def push(self, l, s, ts):
+        rc, r = self.ps.push(self.g, ts, l)
+        return rc, int(r.staleness), int(r.applied)
+
+    def pull_ts(self):
+        return self.ps.ts
+
+
+@pytest.mark.parametrize("name", list(configs.ALL))
+def test_control_plane_equals_oracle_on_every_workload_trace(name):
+    w = configs.ALL[name]
+    n = min(w.n_pushes, 6000)
+    learner, step = w.arrival_trace(n)
+    hip, ora = _Control(w, clock_ring=8192), _OracleControl(w)
+    lh = replay.replay(hip, learner, step, w.n_learners, hardsync=w.protocol == "hardsync")
+    lo = replay.replay(ora, learner, step, w.n_learners, hardsync=w.protocol == "hardsync")
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    st = hip.ps.stats()
+    o = ora.ps
+    assert (st.ts_cur, st.n_pushes, st.n_updates, st.pending, st.c) == (o.ts, o.n_pushes, o.n_updates, o.pending, o.c)
+    assert (st.sigma_sum, st.sigma_max) == (o.sigma_sum, o.sigma_max)
+    assert st.bytes_absorbed == o.n_pushes * 4 * w.n_params
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), o.hist)
+    clocks, avg, lr = o.clocks, o.avg_staleness, o.lr_log
+    for u in range(o.n_updates):
+        ts, a, r = hip.ps.vector_clock(u)
+        assert ts == list(clocks[u]) and a == avg[u] and np.float32(r) == lr[u]
+    if o.n_updates:
+        assert st.last_avg_staleness == avg[-1] and np.float32(st.last_lr) == lr[-1]
+    with pytest.raises(R.RudraError):
+        hip.ps.vector_clock(o.n_updates)          # has not happened yet
+
+
+def test_clock_ring_evicts_old_updates():
+    ps = R.ParameterServer(1, 2, n_split=2, flags=B.FLAG_CONTROL_ONLY, clock_ring=4)
+    for i in range(10):
+        ps.push_gradient(0, i, 0)
+    assert ps.vector_clock(9)[0] == [9] and ps.vector_clock(6)[0] == [6]
+    with pytest.raises(R.RudraError) as e:
+        ps.vector_clock(5)
+    assert e.value.status == B.ERANGE
+
+
+def test_set_lr_changes_later_updates_only():
+    ps = R.ParameterServer(1, 1, protocol=B.HARDSYNC, lr_mode=B.LR_CONST, alpha0=0.5, flags=B.FLAG_CONTROL_ONLY)
+    assert ps.push_gradient(0, 0, 0)[1].lr_used == 0.5
+    ps.set_lr(0.05)
+    assert np.float32(ps.push_gradient(0, 1, 0)[1].lr_used) == np.float32(0.05)
+    assert ps.vector_clock(0)[2] == 0.5

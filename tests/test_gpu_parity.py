@@ -1,0 +1,270 @@
+"""Parity of the HIP path (called through the C ABI) with the CPU oracle, element by element, on the same
+seeded inputs.  Bar: theta and v within 1e-5 * ||.||_inf of the binary32 oracle; timestamps, staleness,
+vector clocks, histogram, counters and learning rates bit-exact.  (Both sides evaluate the same sequence of
+individually rounded binary32 operations, so in practice the floats are bit-identical too; that stronger
+property is asserted separately so a regression shows which of the two broke.)"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.adapter import OracleServer
+from synth import configs, gradgen, replay
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def hipmod():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1509_04210_amd import binding, learners
+    binding.lib()            # fails loudly if the HIP library is not built
+    gradgen.device_lib()
+    return learners
+
+
+def _with(w, **kw):
+    return type(w)(**{**w.__dict__, **kw})
+
+
+def _compare(hip, ora, w, check_bits=True):
+    th = hip.weights().cpu().numpy()
+    ref = ora.ps.theta
+    scale = np.abs(ref).max()
+    err = np.abs(th.astype(np.float64) - ref.astype(np.float64)).max()
+    assert err <= TOL * scale, f"theta: max abs err {err:.3e} vs {TOL * scale:.3e}"
+    if w.momentum != 0:
+        ve = hip.velocity().cpu().numpy()
+        vref = ora.ps.velocity
+        verr = np.abs(ve.astype(np.float64) - vref.astype(np.float64)).max()
+        assert verr <= TOL * max(np.abs(vref).max(), 1e-30), f"v: max abs err {verr:.3e}"
+        if check_bits:
+            assert np.array_equal(ve, vref), "velocity not bit-identical"
+    if check_bits:
+        assert np.array_equal(th, ref), "theta not bit-identical"
+    st = hip.ps.stats()
+    o = ora.ps
+    assert (st.ts_cur, st.n_pushes, st.n_updates, st.pending, st.c) == (o.ts, o.n_pushes, o.n_updates, o.pending, o.c)
+    assert (st.sigma_sum, st.sigma_max) == (o.sigma_sum, o.sigma_max)
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), o.hist)
+    clocks, avg, lr = o.clocks, o.avg_staleness, o.lr_log
+    for u in range(max(0, o.n_updates - 1024), o.n_updates):
+        ts, a, r = hip.ps.vector_clock(u)
+        assert ts == list(clocks[u]) and a == avg[u] and np.float32(r) == lr[u]
+    return err / scale
+
+
+def _run_both(learners, w, flags=0, n_pushes=None, **launch):
+    learner, step = w.arrival_trace(n_pushes)
+    hard = w.protocol == "hardsync"
+    hip, ora = learners.HipServer(w, flags=flags, **launch), OracleServer(w)
+    lh = replay.replay(hip, learner, step, w.n_learners, hardsync=hard)
+    lo = replay.replay(ora, learner, step, w.n_learners, hardsync=hard)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    return hip, ora
+
+
+# ---------------------------------------------------------------- inputs: device generator == numpy generator
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 100_003])
+def test_device_generator_is_bit_identical_to_numpy(hipmod, n):
+    for tail_per, std in [(0, 1e-3), (100, 1e-4)]:
+        key = gradgen.stream_key(99, gradgen.TAG_GRAD, 3, n)
+        buf = torch.full((n + 8,), 7.0, dtype=torch.float32, device="cuda")
+        gradgen.fill_device(buf.data_ptr(), n, key, std, tail_per, 100.0, stream=0)
+        torch.cuda.synchronize()
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[:n], gradgen.vector(key, n, std, tail_per, 100.0))
+        assert np.all(got[n:] == 7.0)       # nothing written past the end
+
+
+# ---------------------------------------------------------------- every workload, at a size the oracle replays in seconds
+# sizes span several 1024-vector tiles and leave a ragged tail (P % 4 != 0, last tile partly filled)
+SMALL = {
+    "C1": (configs.C1, 131072, 256),                 # the tiny config at its real size
+    "C2": (configs.C2, 70_003, 900),                 # hardsync, momentum
+    "C3-n1": (configs.C3(1), 50_001, 600),
+    "C3-n2": (configs.C3(2), 50_002, 600),
+    "C3-n4": (configs.C3(4), 50_003, 600),           # c = floor(30/4) = 7
+    "C3-n30": (configs.C3(30), 50_005, 600),
+    "C4": (configs.C4, 90_007, 360),                 # c = 18, heavy-tailed gradients, momentum
+    "C5": (configs.C5, 90_001, 700),                 # c = 1, momentum + weight penalty, staleness up to ~100
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_workload_parity_small(hipmod, name):
+    base, P, n = SMALL[name]
+    w = base.scaled(n_params=P, n_pushes=n)
+    hip, ora = _run_both(hipmod, w)
+    rel = _compare(hip, ora, w)
+    print(f"{name}: P={P} pushes={n} updates={ora.ps.ts} rel err={rel:.2e}")
+    hip.close()
+
+
+def test_c2_full_size_hardsync(hipmod):
+    """The 1.0M-parameter hardsync workload at its real size (a reduced number of rounds keeps the CPU replay short)."""
+    w = configs.C2.scaled(n_pushes=30 * 40)
+    hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    assert hip.ps.stats().sigma_max == 0
+    hip.close()
+
+
+# ---------------------------------------------------------------- launch shapes, c from 1 past the fused limit, modes
+@pytest.mark.parametrize("block,unroll,vec,grid", [(64, 1, 1, 0), (256, 4, 1, 0), (256, 8, 1, 0), (512, 2, 2, 0),
+                                                    (1024, 2, 4, 0), (256, 4, 2, 3), (128, 1, 4, 7), (256, 2, 1, 1)])
+def test_launch_shapes_give_the_same_bits(hipmod, block, unroll, vec, grid):
+    w = _with(configs.C4.scaled(n_params=33_331, n_pushes=18 * 4), weight_decay=5e-4)
+    hip, ora = _run_both(hipmod, w, launch_block=block, launch_unroll=unroll, launch_vec=vec, launch_grid=grid)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 5, 8, 9, 13, 17, 31, 64, 65, 70, 130])
+def test_gradients_per_update_sweep(hipmod, c):
+    """c below, at and beyond the 64 gradients one launch takes (larger sets are folded through the accumulator)."""
+    w = _with(configs.C3(1).scaled(n_params=9_999, n_pushes=3 * c + 1), n_learners=max(c, 2), c_override=c,
+              momentum=0.9)
+    hip, ora = _run_both(hipmod, w, launch_unroll=8)
+    _compare(hip, ora, w)
+    assert hip.ps.stats().pending == (1 if c > 1 else 0)
+    hip.close()
+
+
+@pytest.mark.parametrize("lr_mode", ["const", "static_n", "avg_staleness", "per_gradient"])
+@pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 5e-4)])
+def test_rate_modes(hipmod, lr_mode, momentum, wd):
+    w = _with(configs.C3(4).scaled(n_params=20_002, n_pushes=350), lr_mode=lr_mode, momentum=momentum,
+              weight_decay=wd, alpha0=0.05)
+    hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+@pytest.mark.parametrize("lr_mode", ["avg_staleness", "per_gradient"])
+def test_accumulate_at_push_gives_the_same_bits_as_the_fused_path(hipmod, lr_mode):
+    from paper_1509_04210_amd import binding as B
+    w = _with(configs.C3(2).scaled(n_params=40_001, n_pushes=300), lr_mode=lr_mode, momentum=0.9)
+    hip, ora = _run_both(hipmod, w, flags=B.FLAG_PUSH_ACCUMULATE)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 8, 1023, 1024, 1025, 4099])
+def test_tiny_and_ragged_vectors(hipmod, P):
+    w = _with(configs.C5.scaled(n_params=P, n_pushes=40), n_learners=5, n_split=2)
+    hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+def test_leftover_gradients_stay_pending(hipmod):
+    w = configs.C3(1).scaled(n_params=5000, n_pushes=2 * 30 + 11)
+    hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    st = hip.ps.stats()
+    assert st.pending == 11 and st.ts_cur == 2
+    hip.close()
+
+
+# ---------------------------------------------------------------- boundary behaviour on the device
+def test_rejected_pushes_leave_the_weights_alone(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = _with(configs.C2.scaled(n_params=1000, n_pushes=6), n_learners=3)
+    hip = hipmod.HipServer(w)
+    before = hip.weights().cpu().numpy()
+    g = torch.ones(1004, dtype=torch.float32, device="cuda")
+    assert hip.ps.push_gradient(g.data_ptr() + 4, 0, 0)[0] == B.EINVAL          # not 16-byte aligned
+    assert hip.ps.push_gradient(0, 0, 0)[0] == B.EINVAL                         # null
+    assert hip.ps.push_gradient(g.data_ptr(), 1, 0)[0] == B.EFUTURE_TS
+    assert hip.ps.push_gradient(g.data_ptr(), 0, 9)[0] == B.EINVAL
+    assert hip.ps.push_gradient(g.data_ptr(), 0, 0)[0] == B.OK
+    assert hip.ps.push_gradient(g.data_ptr(), 0, 0)[0] == B.EHARDSYNC_DUP
+    hip.ps.sync()
+    assert np.array_equal(hip.weights().cpu().numpy(), before)
+    assert hip.ps.push_gradient(g.data_ptr(), 0, 1)[0] == B.OK
+    rc, r = hip.ps.push_gradient(g.data_ptr(), 0, 2)
+    assert rc == B.OK and r.applied == 1 and r.ts_after == 1
+    assert hip.ps.push_gradient(g.data_ptr(), 0, 0)[0] == B.EHARDSYNC_STALE
+    after = hip.weights().cpu().numpy()
+    want = before - np.float32(w.alpha0) * (np.float32(3.0) * (np.float32(1) / np.float32(3)))
+    assert np.array_equal(after, want.astype(np.float32))
+    st = hip.ps.stats()
+    assert st.n_rejected == 6 and st.n_pushes == 3 and st.last_hip_error == 0
+    hip.close()
+
+
+def test_pull_returns_weights_with_their_timestamp(hipmod):
+    w = configs.C1.scaled(n_params=4097, n_pushes=8)
+    hip, ora = _run_both(hipmod, w, n_pushes=4)            # exactly one update
+    dst = torch.zeros(4097, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    ts = hip.ps.pull_weights(dst.data_ptr())
+    hip.ps.sync()
+    assert ts == 1 and np.array_equal(dst.cpu().numpy(), ora.ps.theta)
+    assert hip.ps.pull_weights(0) == 1                     # timestamp inquiry: no copy
+    hip.close()
+
+
+def test_fused_norms(hipmod):
+    from paper_1509_04210_amd import binding as B
+    for shape in (dict(), dict(launch_block=512, launch_vec=2, launch_grid=5)):
+        w = configs.C5.scaled(n_params=77_777, n_pushes=30)
+        hip, ora = _run_both(hipmod, w, flags=B.FLAG_STATS_NORMS, **shape)
+        _compare(hip, ora, w)
+        st, ref = hip.ps.stats(), ora.ps.norms()
+        assert st.norms_valid == 1
+        for got, want in [(st.theta_sq, ref["theta_sq"]), (st.v_sq, ref["v_sq"]), (st.gbar_sq, ref["gbar_sq"])]:
+            assert abs(got - want) <= 1e-5 * want
+        assert st.theta_inf == ref["theta_inf"]            # a max of binary32 values: exact
+        hip.close()
+
+
+def test_kernel_timer_counts_every_update(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = configs.C5.scaled(n_params=50_000, n_pushes=300)    # more updates than the timer ring holds
+    hip, ora = _run_both(hipmod, w, flags=B.FLAG_TIME_KERNELS)
+    _compare(hip, ora, w)
+    st = hip.ps.stats()
+    assert st.kernel_launches == 300 and 0 < st.kernel_ms < 300 * 5.0
+    hip.close()
+
+
+# ---------------------------------------------------------------- full size, in the launch shape bench.py times
+def _sample_indices(P, seed, block_tile=1024 * 4):
+    rng = np.random.default_rng(seed)
+    head = np.arange(0, 2 * block_tile)                     # first two tiles
+    tail = np.arange(P - block_tile - 7, P)                 # last tile and the ragged end
+    rand = rng.integers(0, P, size=16384)
+    return np.unique(np.concatenate([head, tail, rand])).astype(np.uint64)
+
+
+@pytest.mark.parametrize("name,n_pushes", [("C4", 18 * 60), ("C5", 1500)])
+def test_full_size_72m_parity_on_sampled_elements(hipmod, name, n_pushes):
+    """72M parameters, default launch shape (the one bench.py times).  The update is elementwise, so the
+    oracle replays the same trace on ~25k sampled positions (first tiles, last tile + tail, random) and
+    every sampled theta/v must match; integer outputs are compared in full."""
+    w = configs.ALL[name].scaled(n_pushes=n_pushes)
+    idx = _sample_indices(w.n_params, 7)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w), OracleServer(w, index=idx)
+    lh = replay.replay(hip, learner, step, w.n_learners)
+    lo = replay.replay(ora, learner, step, w.n_learners)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    sel = torch.from_numpy(idx.astype(np.int64)).cuda()
+    th = hip.weights()[sel].cpu().numpy()
+    ve = hip.velocity()[sel].cpu().numpy()
+    ref, vref = ora.ps.theta, ora.ps.velocity
+    assert np.abs(th.astype(np.float64) - ref).max() <= TOL * np.abs(ref).max()
+    assert np.abs(ve.astype(np.float64) - vref).max() <= TOL * np.abs(vref).max()
+    assert np.array_equal(th, ref) and np.array_equal(ve, vref)
+    st = hip.ps.stats()
+    assert (st.ts_cur, st.n_pushes, st.sigma_sum, st.sigma_max) == (ora.ps.ts, ora.ps.n_pushes, ora.ps.sigma_sum, ora.ps.sigma_max)
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), ora.ps.hist)
+    # a property that holds at any size: untouched memory beyond P does not exist to check, but the state must be finite
+    full = hip.weights()
+    assert bool(torch.isfinite(full).all())
+    hip.close()
