@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the Rudra parameter-server update path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one applyUpdate of the 72M-parameter 1-softsync workload (C4: lambda = 18 learners, c = 18
+gradients per update, momentum 0.9, staleness-modulated rate): 18 pushGradient calls through the C ABI
+(staleness, vector clock, rate on the host) and the fused sumGradients+applyUpdate kernel they trigger.
+Gradients are synthetic (seeded; 64 distinct 288 MB vectors pre-generated in HBM and cycled, far beyond
+the 256 MB Infinity Cache) and already resident when the timed region starts; the arrival order is the
+workload's seeded Exp(1) trace.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "PS applyUpdates/sec and absorbed gradient GB/s (% HBM peak), 72M fp32 params"
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
+
+# HBM bytes per applyUpdate launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
+# same counters' reading for a plain copy kernel of known size; see profiles/apply_update_C4_traffic.md.
+# None until measured.
+MEASURED_TRAFFIC_BYTES = {"C4": None, "C5": None}
+
+
+def algorithmic_bytes_per_update(w) -> int:
+    """Each of the c gradients read once, theta read+written once, v read+written once when there is momentum."""
+    return w.n_params * (4 * w.c + 8 + (8 if w.momentum != 0 else 0))
+
+
+def run_gpu(w, steps, warmup, ring=64, flags=0, **launch):
+    """Replays (warmup+steps)*c pushes of the workload's arrival trace; returns timings of the last `steps` updates."""
+    import torch
+    from paper_1509_04210_amd.learners import HipServer
+
+    c = w.c
+    learner, step = w.arrival_trace((warmup + steps) * c)
+    hip = HipServer(w, flags=flags, pregenerated=max(ring, c + 1), **launch)
+    ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
+    nbuf = len(bufs)
+    learner_ts = [0] * w.n_learners
+    hard = w.protocol == "hardsync"
+    learner = [int(x) for x in learner]
+
+    def run_range(lo, hi):
+        nonlocal learner_ts
+        push = ps.push_gradient
+        for i in range(lo, hi):
+            l = learner[i]
+            rc, res = push(bufs[i % nbuf], learner_ts[l], l)
+            if rc != 0:
+                raise RuntimeError(f"push {i} rejected: {rc}")
+            if hard and res.applied:
+                learner_ts = [res.ts_after] * w.n_learners
+            else:
+                learner_ts[l] = res.ts_after
+
+    run_range(0, warmup * c)
+    ps.sync()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(hip.stream)
+    t0 = time.perf_counter()
+    run_range(warmup * c, (warmup + steps) * c)
+    e1.record(hip.stream)
+    ps.sync()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    st = ps.stats()
+    assert st.n_updates == warmup + steps, (st.n_updates, warmup + steps)
+    out = dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * c, sigma_mean=st.sigma_mean,
+               kernel_ms=st.kernel_ms, kernel_launches=st.kernel_launches)
+    # sanity: the state is finite and moved
+    chk = hip.weights()
+    out["theta_absmax"] = float(chk.abs().max())
+    assert bool(torch.isfinite(chk).all())
+    hip.close()
+    del hip, chk
+    torch.cuda.empty_cache()
+    return out
+
+
+def run_cpu_oracle(w, n_updates=30, n_distinct=3):
+    """The CPU oracle as it stands, single thread, on the full-size vector: `n_updates` applyUpdates of the same
+    workload.  Gradient materialisation is excluded from the timing (as on the GPU)."""
+    import numpy as np
+    import torch
+    from oracle.adapter import LR_MODE, PROTOCOL
+    from oracle import OraclePS
+    from synth import gradgen
+
+    P = w.n_params
+    dev = torch.device("cuda", 0)
+    buf = torch.empty(P, dtype=torch.float32, device=dev)
+
+    def device_vector(key, std, tail_per):
+        gradgen.fill_device(buf.data_ptr(), P, key, std, tail_per, w.tail_factor, stream=0)
+        torch.cuda.synchronize()
+        return buf.cpu().numpy()
+
+    init = device_vector(w.init_key(), w.init_std, 0)
+    grads = [device_vector(w.grad_key(l, 0), w.grad_std, w.tail_per) for l in range(n_distinct)]
+    ps = OraclePS(init, w.n_learners, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode], w.alpha0, w.lr_scale,
+                  w.momentum, w.weight_decay, w.c_override)
+    learner, _ = w.arrival_trace(n_updates * w.c)
+    learner_ts = [0] * w.n_learners
+    t0 = time.perf_counter()
+    for i, l in enumerate(learner):
+        rc, res = ps.push(grads[i % n_distinct], learner_ts[int(l)], int(l))
+        assert rc == 0
+        learner_ts[int(l)] = res.ts_after
+    dt = time.perf_counter() - t0
+    assert ps.ts == n_updates
+    return dict(value=n_updates / dt, seconds=dt, updates=n_updates)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4", choices=["C4", "C5"])
+    ap.add_argument("--ring", type=int, default=64)
+    ap.add_argument("--block", type=int, default=0)
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--vec", type=int, default=0)
+    ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (the parameter-server update path does not span GPUs here); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1509_04210_amd import binding as B
+    from synth import configs
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid)
+    w = configs.ALL[args.workload]
+    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, **launch)
+    bytes_upd = algorithmic_bytes_per_update(w)
+    ups = r["updates"] / r["wall_s"]
+    kernel_ms = r["event_ms"] / r["updates"]     # the timed region is back-to-back applyUpdate launches only
+    achieved = bytes_upd / (kernel_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    line = {
+        "metric": METRIC, "value": ups, "unit": "applyUpdates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * r["wall_s"] / r["updates"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: P={w.n_params} fp32, lambda={w.n_learners}, {w.n_split}-softsync (c={w.c}), "
+                               f"momentum={w.momentum}, wd={w.weight_decay}, lr=alpha0/max(1,<sigma>), "
+                               f"ring of {max(args.ring, w.c + 1)} pre-generated gradients",
+                   "pushes_per_step": w.c, "launch": {k: v for k, v in launch.items() if v}},
+        "absorbed_gradient_GBps": r["pushes"] * 4 * w.n_params / r["wall_s"] / 1e9,
+        "pushes_per_s": r["pushes"] / r["wall_s"],
+        "mean_staleness": r["sigma_mean"],
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "kernel": "apply_update_kernel", "bytes_per_launch": bytes_upd, "avg_launch_ms": kernel_ms},
+    }
+    if not args.no_extra:
+        # per-launch HIP events around every applyUpdate (library flag), same workload
+        rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=B.FLAG_TIME_KERNELS, **launch)
+        k_ms = rt["kernel_ms"] / max(1, rt["kernel_launches"])
+        line["roofline"]["per_launch_event_ms"] = k_ms
+        line["roofline"]["per_launch_event_GBps"] = bytes_upd / (k_ms * 1e-3) / 1e9
+        # the lambda-softsync stress workload (c = 1, momentum + weight penalty), same protocol of measurement
+        other = configs.C5 if args.workload == "C4" else configs.C4
+        ro = run_gpu(other, 1000 if other.c == 1 else 200, 10, ring=args.ring, **launch)
+        bo = algorithmic_bytes_per_update(other)
+        o_ms = ro["event_ms"] / ro["updates"]
+        line["extra"] = {other.name: {
+            "applyUpdates_per_s": ro["updates"] / ro["wall_s"], "absorbed_gradient_GBps": ro["pushes"] * 4 * other.n_params / ro["wall_s"] / 1e9,
+            "avg_launch_ms": o_ms, "achieved_GBps": bo / (o_ms * 1e-3) / 1e9, "frac": bo / (o_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "bytes_per_launch": bo, "mean_staleness": ro["sigma_mean"]}}
+    if not args.no_cpu_baseline:
+        cb = run_cpu_oracle(w)
+        line["cpu_baseline"] = {"value": cb["value"], "unit": "applyUpdates/s", "cores": 1, "kind": "oracle",
+                                "sample": f"{cb['updates']} applyUpdates ({cb['updates'] * w.c} pushes) of the same workload on the full "
+                                          f"{w.n_params}-element vector, single thread, {cb['seconds']:.1f} s, gradients pre-materialised",
+                                "GBps": cb["value"] * bytes_upd / 1e9}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -4,8 +4,9 @@
 // momentum velocity v) once, and does all of Eq. 4 (average of c gradients) and Eq. 1c
 // (theta <- theta - alpha * gbar), plus the momentum and weight-penalty terms of Sec. 4.2, in
 // registers.  The path is a pure HBM stream: (c+5) flops per (4c+16) bytes, so there is no
-// MFMA and no LDS staging here; what matters is 128-bit coalesced access, many independent
-// loads in flight per lane, and a launch with far more workgroups than the 256 CUs.
+// MFMA and no LDS staging here; what matters is 128-bit coalesced access, streaming cache
+// policy, independent loads in flight per lane, and a launch of many small workgroups (one
+// 64-lane wavefront each by default: measured 6-8 % faster than 256-thread workgroups).
 //
 // Arithmetic contract (must stay bit-compatible with a sequential binary32 evaluation):
 //   s    = w_1*g_1[k]; s = s + w_l*g_l[k]  for l = 2..c, in arrival order   (w_l only in the
@@ -45,12 +46,18 @@ struct UpdateArgs {
   float inv_c, lr, momentum, weight_decay;
 };
 
-// Gradients are read exactly once per update: mark the loads non-temporal so they do not
-// displace theta/v lines in L2 / Infinity Cache.
+// Cache policy.  Every byte this kernel touches is used exactly once per launch (gradients are
+// read once; theta and v are read, updated and written back, and the next launch comes only
+// after c more pushes of 4P bytes each), so all vector memory accesses carry the non-temporal
+// hint: lines stream through L2 instead of displacing each other.  Measured on MI355X at 72M
+// parameters: non-temporal stores are worth about 8 % of bandwidth, non-temporal gradient
+// loads another 4 %; the scope bits (sc0/sc1) make no difference.
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
 __device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
+__device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return __builtin_nontemporal_load(p + iv); }
+__device__ __forceinline__ void store_state4(floatx4* p, uint64_t iv, floatx4 x) { __builtin_nontemporal_store(x, p + iv); }
 
 // Sum of the c gradients at V vector positions, in arrival order.  Loads are issued U
 // gradients x V positions at a time before the first add that needs them, so each lane keeps
@@ -196,26 +203,26 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       for (int v = 0; v < V; ++v) iv[v] = base + (uint64_t)v * blockDim.x;
 #pragma unroll
       for (int v = 0; v < V; ++v) {
-        th[v] = theta4[iv[v]];
-        if (MOMENTUM) ve[v] = vel4[iv[v]];
+        th[v] = load_state4(theta4, iv[v]);
+        if (MOMENTUM) ve[v] = load_state4(vel4, iv[v]);
       }
       sum_gradients<WEIGHTED, U, V>(gs, a.c, iv, s);
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         update_vec4<MOMENTUM, STATS>(s[v], th[v], ve[v], a, n);
-        theta4[iv[v]] = th[v];
-        if (MOMENTUM) vel4[iv[v]] = ve[v];
+        store_state4(theta4, iv[v], th[v]);
+        if (MOMENTUM) store_state4(vel4, iv[v], ve[v]);
       }
     } else {
       for (int v = 0; v < V; ++v) {
         const uint64_t i1[1] = {base + (uint64_t)v * blockDim.x};
         if (i1[0] >= n4) break;
-        floatx4 th = theta4[i1[0]], ve = {0.f, 0.f, 0.f, 0.f}, s[1];
-        if (MOMENTUM) ve = vel4[i1[0]];
+        floatx4 th = load_state4(theta4, i1[0]), ve = {0.f, 0.f, 0.f, 0.f}, s[1];
+        if (MOMENTUM) ve = load_state4(vel4, i1[0]);
         sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
         update_vec4<MOMENTUM, STATS>(s[0], th, ve, a, n);
-        theta4[i1[0]] = th;
-        if (MOMENTUM) vel4[i1[0]] = ve;
+        store_state4(theta4, i1[0], th);
+        if (MOMENTUM) store_state4(vel4, i1[0], ve);
       }
     }
   }
@@ -248,7 +255,7 @@ __global__ void sum_gradients_kernel(const GradSet gs, const UpdateArgs a) {
       if (i1[0] >= n4) break;
       floatx4 s[1];
       sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
-      out4[i1[0]] = s[0];
+      store_state4(out4, i1[0], s[0]);
     }
   }
   if (blockIdx.x == 0) {

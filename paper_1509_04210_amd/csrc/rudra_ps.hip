@@ -23,7 +23,7 @@ using rudra::UpdateArgs;
 
 namespace {
 
-constexpr uint32_t kDefaultBlock = 256;
+constexpr uint32_t kDefaultBlock = 64;   // one wavefront per workgroup: finest dispatch granularity, measured fastest
 constexpr uint32_t kDefaultUnroll = 4;
 constexpr uint32_t kDefaultVec = 1;
 constexpr uint32_t kDefaultClockRing = 1024;

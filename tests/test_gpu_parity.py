@@ -80,7 +80,7 @@ def test_device_generator_is_bit_identical_to_numpy(hipmod, n):
 
 
 # ---------------------------------------------------------------- every workload, at a size the oracle replays in seconds
-# sizes span several 1024-vector tiles and leave a ragged tail (P % 4 != 0, last tile partly filled)
+# sizes span many tiles (64 to 4096 float4 positions each, depending on the launch shape) and leave a ragged tail
 SMALL = {
     "C1": (configs.C1, 131072, 256),                 # the tiny config at its real size
     "C2": (configs.C2, 70_003, 900),                 # hardsync, momentum
