@@ -25,10 +25,10 @@ if ROOT not in sys.path:
 METRIC = "PS applyUpdates/sec and absorbed gradient GB/s (% HBM peak), 72M fp32 params"
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
 
-# HBM bytes per applyUpdate launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by the
-# same counters' reading for a plain copy kernel of known size; see profiles/apply_update_C4_traffic.md.
-# None until measured.
-MEASURED_TRAFFIC_BYTES = {"C4": None, "C5": None}
+# HBM bytes per applyUpdate launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE), each scaled by
+# the same counter's reading for a plain copy of known size (factors 1.99979 and 1.0); figures and commands in
+# profiles/apply_update_kernel_C4_C5_72M_hbm_traffic.md.  A measured constant, not recomputed at run time.
+MEASURED_TRAFFIC_BYTES = {"C4": 6.3354e9, "C5": 1.43994e9}
 
 
 def algorithmic_bytes_per_update(w) -> int:
@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
+    ap.add_argument("--calibration-copies", type=int, default=0,
+                    help="also run this many plain device copies of P floats (known size: 4P bytes read, 4P written) so that "
+                         "a rocprofv3 --pmc run of this command has a reference reading for FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU (the parameter-server update path does not span GPUs here); "
@@ -171,6 +174,13 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "apply_update_kernel", "bytes_per_launch": bytes_upd, "avg_launch_ms": kernel_ms},
     }
+    if args.calibration_copies:
+        src = torch.empty(w.n_params, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(args.calibration_copies):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_extra:
         # per-launch HIP events around every applyUpdate (library flag), same workload
         rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=B.FLAG_TIME_KERNELS, **launch)

@@ -110,10 +110,10 @@ struct Norms {
 };
 
 // applyUpdate on one element.  The single place where the update rule is written.
-template <bool MOMENTUM, bool STATS>
+template <bool MOMENTUM, bool DECAY, bool STATS>
 __device__ __forceinline__ void update_element(float s, float& th, float& v, const UpdateArgs& a, Norms& n) {
   float gbar = s * a.inv_c;
-  if (a.weight_decay != 0.0f) {
+  if (DECAY) {
     float penalty = a.weight_decay * th;
     gbar = gbar + penalty;
   }
@@ -134,12 +134,12 @@ __device__ __forceinline__ void update_element(float s, float& th, float& v, con
   }
 }
 
-template <bool MOMENTUM, bool STATS>
+template <bool MOMENTUM, bool DECAY, bool STATS>
 __device__ __forceinline__ void update_vec4(const floatx4& s, floatx4& th, floatx4& ve, const UpdateArgs& a, Norms& n) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     float t = th[i], v = MOMENTUM ? ve[i] : 0.f;
-    update_element<MOMENTUM, STATS>(s[i], t, v, a, n);
+    update_element<MOMENTUM, DECAY, STATS>(s[i], t, v, a, n);
     th[i] = t;
     if (MOMENTUM) ve[i] = v;
   }
@@ -185,7 +185,7 @@ __device__ __forceinline__ void block_reduce_norms(const Norms& n, double* parti
 // the c+2 streams.  Workgroups take tiles blockIdx, blockIdx+gridDim, ... (grid-stride); the
 // host normally launches one workgroup per tile.  The last P%4 elements are done by the first
 // lanes of workgroup 0 with scalar accesses.
-template <bool MOMENTUM, bool WEIGHTED, bool STATS, int U, int V>
+template <bool MOMENTUM, bool DECAY, bool WEIGHTED, bool STATS, int U, int V>
 __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t tile = (uint64_t)blockDim.x * V;
@@ -209,7 +209,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       sum_gradients<WEIGHTED, U, V>(gs, a.c, iv, s);
 #pragma unroll
       for (int v = 0; v < V; ++v) {
-        update_vec4<MOMENTUM, STATS>(s[v], th[v], ve[v], a, n);
+        update_vec4<MOMENTUM, DECAY, STATS>(s[v], th[v], ve[v], a, n);
         store_state4(theta4, iv[v], th[v]);
         if (MOMENTUM) store_state4(vel4, iv[v], ve[v]);
       }
@@ -220,7 +220,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
         floatx4 th = load_state4(theta4, i1[0]), ve = {0.f, 0.f, 0.f, 0.f}, s[1];
         if (MOMENTUM) ve = load_state4(vel4, i1[0]);
         sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
-        update_vec4<MOMENTUM, STATS>(s[0], th, ve, a, n);
+        update_vec4<MOMENTUM, DECAY, STATS>(s[0], th, ve, a, n);
         store_state4(theta4, i1[0], th);
         if (MOMENTUM) store_state4(vel4, i1[0], ve);
       }
@@ -231,7 +231,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
     if (k < a.n_params) {
       float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
       float th = a.theta[k], ve = MOMENTUM ? a.vel[k] : 0.f;
-      update_element<MOMENTUM, STATS>(s, th, ve, a, n);
+      update_element<MOMENTUM, DECAY, STATS>(s, th, ve, a, n);
       a.theta[k] = th;
       if (MOMENTUM) a.vel[k] = ve;
     }

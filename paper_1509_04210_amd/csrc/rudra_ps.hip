@@ -117,36 +117,43 @@ LaunchShape shape_for(const rudra_ps* ps) {
   return {(uint32_t)grid, ps->block, tiles};
 }
 
-// ---- kernel dispatch: runtime (momentum, weighted, stats, unroll, vec) -> template instance ----
-template <bool MOM, bool W, bool ST, int U>
+// ---- kernel dispatch: runtime (momentum, decay, weighted, stats, unroll, vec) -> template instance ----
+template <bool MOM, bool WD, bool W, bool ST, int U>
 void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (vec) {
-    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
-    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
-    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, W, ST, U, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
   }
 }
-template <bool MOM, bool W, bool ST>
+template <bool MOM, bool WD, bool W, bool ST>
 void launch_apply_u(uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (unroll) {
-    case 1: launch_apply_v<MOM, W, ST, 1>(vec, s, st, gs, a); break;
-    case 2: launch_apply_v<MOM, W, ST, 2>(vec, s, st, gs, a); break;
-    case 4: launch_apply_v<MOM, W, ST, 4>(vec, s, st, gs, a); break;
-    default: launch_apply_v<MOM, W, ST, 8>(vec, s, st, gs, a); break;
+    case 1: launch_apply_v<MOM, WD, W, ST, 1>(vec, s, st, gs, a); break;
+    case 2: launch_apply_v<MOM, WD, W, ST, 2>(vec, s, st, gs, a); break;
+    case 4: launch_apply_v<MOM, WD, W, ST, 4>(vec, s, st, gs, a); break;
+    default: launch_apply_v<MOM, WD, W, ST, 8>(vec, s, st, gs, a); break;
   }
 }
-void launch_apply(bool mom, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
-                  const GradSet& gs, const UpdateArgs& a) {
-  const int key = (mom ? 4 : 0) | (weighted ? 2 : 0) | (stats ? 1 : 0);
-  switch (key) {
-    case 0: launch_apply_u<false, false, false>(unroll, vec, s, st, gs, a); break;
-    case 1: launch_apply_u<false, false, true>(unroll, vec, s, st, gs, a); break;
-    case 2: launch_apply_u<false, true, false>(unroll, vec, s, st, gs, a); break;
-    case 3: launch_apply_u<false, true, true>(unroll, vec, s, st, gs, a); break;
-    case 4: launch_apply_u<true, false, false>(unroll, vec, s, st, gs, a); break;
-    case 5: launch_apply_u<true, false, true>(unroll, vec, s, st, gs, a); break;
-    case 6: launch_apply_u<true, true, false>(unroll, vec, s, st, gs, a); break;
-    default: launch_apply_u<true, true, true>(unroll, vec, s, st, gs, a); break;
+template <bool MOM, bool WD>
+void launch_apply_ws(bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
+                     const GradSet& gs, const UpdateArgs& a) {
+  if (weighted) {
+    if (stats) launch_apply_u<MOM, WD, true, true>(unroll, vec, s, st, gs, a);
+    else launch_apply_u<MOM, WD, true, false>(unroll, vec, s, st, gs, a);
+  } else {
+    if (stats) launch_apply_u<MOM, WD, false, true>(unroll, vec, s, st, gs, a);
+    else launch_apply_u<MOM, WD, false, false>(unroll, vec, s, st, gs, a);
+  }
+}
+void launch_apply(bool mom, bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s,
+                  hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  if (mom) {
+    if (decay) launch_apply_ws<true, true>(weighted, stats, unroll, vec, s, st, gs, a);
+    else launch_apply_ws<true, false>(weighted, stats, unroll, vec, s, st, gs, a);
+  } else {
+    if (decay) launch_apply_ws<false, true>(weighted, stats, unroll, vec, s, st, gs, a);
+    else launch_apply_ws<false, false>(weighted, stats, unroll, vec, s, st, gs, a);
   }
 }
 void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
@@ -249,7 +256,7 @@ int enqueue_update(rudra_ps* ps, float lr) {
     slot = (uint32_t)(ps->timed_launches % kTimerRing);
     RUDRA_HIP(ps, hipEventRecord(ps->ev_start[slot], ps->stream));
   }
-  launch_apply(ps->cfg.momentum != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
+  launch_apply(ps->cfg.momentum != 0.0f, ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
   RUDRA_HIP(ps, hipGetLastError());
   if (ps->time_kernels) {
     RUDRA_HIP(ps, hipEventRecord(ps->ev_stop[slot], ps->stream));
