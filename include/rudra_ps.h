@@ -89,6 +89,12 @@ typedef struct {
   uint32_t launch_unroll; /* gradient loads issued together per lane: 1, 2, 4 or 8 */
   uint32_t launch_vec;    /* float4 vectors per lane per tile: 1, 2 or 4 */
   uint32_t launch_grid;   /* upper bound on workgroups (grid-stride beyond it); 0 = one tile per workgroup */
+  uint32_t launch_waves_per_cu; /* cap on resident wavefronts per compute unit, 2..32 (enforced by reserving LDS per
+                                   workgroup); 0 = library default.  Fewer resident waves keep fewer DRAM pages open
+                                   at once; see the kernel header for the measured optimum. */
+  uint32_t launch_alternate; /* 1: successive updates walk the vector in opposite directions, so the theta/v lines
+                                written last are the first read next (memory-side cache reuse); 2: always forward;
+                                0 = library default (alternate) */
 } rudra_ps_config_t;
 
 typedef struct {

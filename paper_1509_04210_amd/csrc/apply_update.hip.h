@@ -43,6 +43,7 @@ struct UpdateArgs {
   uint64_t n_params;
   uint64_t ntiles;   // ceil((n_params/4) / (blockDim*V)), computed on the host
   uint32_t c;        // gradients in this launch, 1..kMaxFused
+  uint32_t reverse;  // 1: walk the tiles from the last to the first
   float inv_c, lr, momentum, weight_decay;
 };
 
@@ -56,7 +57,7 @@ __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
 __device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
-__device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return __builtin_nontemporal_load(p + iv); }
+__device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return p[iv]; }
 __device__ __forceinline__ void store_state4(floatx4* p, uint64_t iv, floatx4 x) { __builtin_nontemporal_store(x, p + iv); }
 
 // Sum of the c gradients at V vector positions, in arrival order.  Loads are issued U
@@ -194,7 +195,8 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
   floatx4* __restrict__ vel4 = reinterpret_cast<floatx4*>(a.vel);
   Norms n = {0.f, 0.f, 0.f, 0.f};
 
-  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+  for (uint64_t t0 = blockIdx.x; t0 < ntiles; t0 += gridDim.x) {
+    const uint64_t t = a.reverse ? ntiles - 1 - t0 : t0;
     const uint64_t base = t * tile + threadIdx.x;
     if (base + (uint64_t)(V - 1) * blockDim.x < n4) {  // all V positions of this lane in range
       uint64_t iv[V];

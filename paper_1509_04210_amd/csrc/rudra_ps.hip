@@ -26,6 +26,7 @@ namespace {
 constexpr uint32_t kDefaultBlock = 64;   // one wavefront per workgroup: finest dispatch granularity, measured fastest
 constexpr uint32_t kDefaultUnroll = 4;
 constexpr uint32_t kDefaultVec = 1;
+constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding load bytes per compute unit
 constexpr uint32_t kDefaultClockRing = 1024;
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
 
@@ -53,7 +54,8 @@ struct rudra_ps {
   uint32_t partials_blocks = 0;
 
   // launch shape
-  uint32_t block = kDefaultBlock, unroll = kDefaultUnroll, vec = kDefaultVec, grid_cap = 0;
+  uint32_t block = kDefaultBlock, unroll = kDefaultUnroll, vec = kDefaultVec, grid_cap = 0, waves_per_cu = 0;
+  bool alternate = true;
 
   // protocol state
   uint64_t ts_cur = 0;
@@ -105,7 +107,21 @@ uint32_t gradients_per_update(const rudra_ps_config_t& cfg) {
 struct LaunchShape {
   uint32_t grid, block;
   uint64_t ntiles;
+  uint32_t lds_bytes;  // unused dynamic LDS reserved per workgroup: the occupancy cap
 };
+
+constexpr uint32_t kLdsPerCu = 160u * 1024u;  // gfx950
+constexpr uint32_t kMaxDynamicLds = 64u * 1024u;
+
+// LDS to reserve per workgroup so that at most `waves_per_cu` wavefronts are resident on a CU.
+uint32_t lds_for_occupancy(uint32_t waves_per_cu, uint32_t block) {
+  if (waves_per_cu == 0 || waves_per_cu >= 32) return 0;
+  const uint32_t waves_per_wg = block / 64;
+  uint32_t wgs = waves_per_cu / waves_per_wg;
+  if (wgs == 0) wgs = 1;
+  uint32_t bytes = (kLdsPerCu / wgs) & ~1023u;  // at most `wgs` such workgroups fit
+  return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
+}
 
 LaunchShape shape_for(const rudra_ps* ps) {
   const uint64_t n4 = ps->cfg.n_params >> 2;
@@ -114,16 +130,16 @@ LaunchShape shape_for(const rudra_ps* ps) {
   uint64_t grid = tiles ? tiles : 1;  // the scalar tail still needs workgroup 0
   if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
   if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;  // grid-stride covers the rest
-  return {(uint32_t)grid, ps->block, tiles};
+  return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(ps->waves_per_cu, ps->block)};
 }
 
 // ---- kernel dispatch: runtime (momentum, decay, weighted, stats, unroll, vec) -> template instance ----
 template <bool MOM, bool WD, bool W, bool ST, int U>
 void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (vec) {
-    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
-    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
-    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a); break;
+    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
+    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
+    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
   }
 }
 template <bool MOM, bool WD, bool W, bool ST>
@@ -159,13 +175,13 @@ void launch_apply(bool mom, bool decay, bool weighted, bool stats, uint32_t unro
 void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   // the fold/accumulate path is not the measured one: a single shape (4 loads in flight)
   if (weighted) {
-    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
-    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
-    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
   } else {
-    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 1>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
-    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 2>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
-    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 4>), dim3(s.grid), dim3(s.block), 0, st, gs, a);
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
   }
 }
 
@@ -245,6 +261,7 @@ int enqueue_update(rudra_ps* ps, float lr) {
   a.c = n;
   a.inv_c = 1.0f / (float)ps->c;  // Eq. 4: the mean is over all c gradients of the update
   a.lr = lr;
+  a.reverse = (ps->alternate && (ps->n_updates & 1)) ? 1u : 0u;
   const LaunchShape s = shape_for(ps);
   a.ntiles = s.ntiles;
   uint32_t slot = 0;
@@ -283,6 +300,8 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->launch_unroll && c->launch_unroll != 1 && c->launch_unroll != 2 && c->launch_unroll != 4 && c->launch_unroll != 8)
     return RUDRA_EINVAL;
   if (c->launch_vec && c->launch_vec != 1 && c->launch_vec != 2 && c->launch_vec != 4) return RUDRA_EINVAL;
+  if (c->launch_alternate > 2) return RUDRA_EINVAL;
+  if (c->launch_waves_per_cu && (c->launch_waves_per_cu < 2 || c->launch_waves_per_cu > 32)) return RUDRA_EINVAL;
   if ((c->launch_unroll ? c->launch_unroll : kDefaultUnroll) * (c->launch_vec ? c->launch_vec : kDefaultVec) > 8)
     return RUDRA_EINVAL;  // more 16-byte loads per lane than the register file holds without spilling
   if (c->flags & ~(uint32_t)(RUDRA_FLAG_STATS_NORMS | RUDRA_FLAG_PUSH_ACCUMULATE | RUDRA_FLAG_CONTROL_ONLY | RUDRA_FLAG_TIME_KERNELS))
@@ -333,6 +352,18 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   if (config->launch_unroll) ps->unroll = config->launch_unroll;
   if (config->launch_vec) ps->vec = config->launch_vec;
   ps->grid_cap = config->launch_grid;
+  ps->alternate = config->launch_alternate != 2;
+  if (config->launch_waves_per_cu) {
+    ps->waves_per_cu = config->launch_waves_per_cu;
+  } else {
+    // about kInFlightKiBPerCu KiB of loads in flight per CU: each resident wave has theta, v and up to `unroll`
+    // gradient loads (1 KiB each) outstanding
+    const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (config->momentum != 0.0f ? 1u : 0u);
+    const uint32_t waves_per_wg = ps->block / 64;
+    uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
+    w = std::max(w, std::max(4u, waves_per_wg));
+    ps->waves_per_cu = std::min(w, 32u);
+  }
   ps->ring = config->clock_ring ? config->clock_ring : kDefaultClockRing;
   try {
     ps->open_clock.assign(ps->c, 0);
