@@ -4,9 +4,8 @@
 // momentum velocity v) once, and does all of Eq. 4 (average of c gradients) and Eq. 1c
 // (theta <- theta - alpha * gbar), plus the momentum and weight-penalty terms of Sec. 4.2, in
 // registers.  The path is a pure HBM stream: (c+5) flops per (4c+16) bytes, so there is no
-// MFMA and no LDS staging here; what matters is 128-bit coalesced access, streaming cache
-// policy, independent loads in flight per lane, and a launch of many small workgroups (one
-// 64-lane wavefront each by default: measured 6-8 % faster than 256-thread workgroups).
+// MFMA and no LDS staging here; what matters is 128-bit coalesced access, the cache policy of
+// each stream, and how many tiles are in flight at once (see "Cache policy" below).
 //
 // Arithmetic contract (must stay bit-compatible with a sequential binary32 evaluation):
 //   s    = w_1*g_1[k]; s = s + w_l*g_l[k]  for l = 2..c, in arrival order   (w_l only in the
@@ -47,12 +46,17 @@ struct UpdateArgs {
   float inv_c, lr, momentum, weight_decay;
 };
 
-// Cache policy.  Every byte this kernel touches is used exactly once per launch (gradients are
-// read once; theta and v are read, updated and written back, and the next launch comes only
-// after c more pushes of 4P bytes each), so all vector memory accesses carry the non-temporal
-// hint: lines stream through L2 instead of displacing each other.  Measured on MI355X at 72M
-// parameters: non-temporal stores are worth about 8 % of bandwidth, non-temporal gradient
-// loads another 4 %; the scope bits (sc0/sc1) make no difference.
+// Cache policy (measured on MI355X at 72M parameters, c = 18 and c = 1):
+//   gradients   read once, never again: non-temporal loads (+4 %).
+//   theta, v    written with non-temporal stores (+8 %: the two write streams, not the c read streams, are what
+//               costs bandwidth in this access mix) but read with ordinary loads, because successive updates walk
+//               the vector in opposite directions (UpdateArgs::reverse): the lines written last by update i are the
+//               first read by update i+1 and part of them is still in the memory-side cache (+5 % at c = 18,
+//               +9 % at c = 1).
+//   scope bits (sc0/sc1) make no difference (all 512 load/load/store policy combinations were tried).
+// Launch shape: one 64-lane wavefront per workgroup (6-8 % faster than 256-thread workgroups), and the host caps the
+// resident waves per CU (by reserving unused LDS) so that about 48 KiB of loads are in flight per CU: more
+// concurrent tiles keep more DRAM pages open at once and lose 3-6 %.
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
