@@ -28,21 +28,20 @@ OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM = 0, -1, -2, -3, 
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-std=c11", "-Wall", "-Wextra"]
 
 
-def build(force: bool = False, extra_defines=()) -> str:
+def build(force: bool = False, src: str = _SRC, out: str = _LIB) -> str:
     """Compile the oracle twice (binary32 and binary64 state) into one shared object."""
-    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
-        return _LIB
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(src):
+        return out
     objs = []
     for real, prefix in (("float", "oracle32_"), ("double", "oracle64_")):
-        obj = os.path.join(_HERE, f"rudra_oracle_{prefix}.o")
-        cmd = ["gcc", *CFLAGS, f"-DORACLE_REAL={real}", f"-DORACLE_PREFIX={prefix}",
-               *[f"-D{d}" for d in extra_defines], "-c", _SRC, "-o", obj]
+        obj = out + f".{prefix}.o"
+        cmd = ["gcc", *CFLAGS, f"-DORACLE_REAL={real}", f"-DORACLE_PREFIX={prefix}", "-c", src, "-o", obj]
         subprocess.run(cmd, check=True)
         objs.append(obj)
-    subprocess.run(["gcc", "-shared", "-o", _LIB, *objs], check=True)
+    subprocess.run(["gcc", "-shared", "-o", out, *objs, "-lm"], check=True)
     for o in objs:
         os.remove(o)
-    return _LIB
+    return out
 
 
 class _Config(C.Structure):
@@ -63,7 +62,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # RUDRA_ORACLE_LIB: a prebuilt variant of this same source (the mutation test plants mistakes in copies
+        # of rudra_oracle.c and checks that the pins catch them)
+        _lib = C.CDLL(os.environ.get("RUDRA_ORACLE_LIB") or build())
         for p in ("oracle32_", "oracle64_"):
             f = lambda n: getattr(_lib, p + n)
             f("create").argtypes = [C.POINTER(_Config), C.c_void_p, C.POINTER(C.c_void_p)]
