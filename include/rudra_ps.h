@@ -33,11 +33,11 @@ typedef struct rudra_ps rudra_ps_t; /* opaque; created and destroyed by the libr
 
 /* Synchronisation protocol (Sec. 3.1). */
 enum rudra_protocol {
-  RUDRA_HARDSYNC = 0, /* one gradient from each of the lambda learners per step, Eq. 2; staleness 0 */
-  RUDRA_SOFTSYNC = 1  /* n-softsync: update after c = floor(lambda/n) gradients, Eq. 4; n = lambda is Async, Eq. 3 */
+  RUDRA_HARDSYNC = 0, /* one gradient from each of the lambda learners per step, Eq. 3; staleness 0 */
+  RUDRA_SOFTSYNC = 1  /* n-softsync: update after c = floor(lambda/n) gradients, Eq. 5; n = lambda is Async, Eq. 4 */
 };
 
-/* How the learning rate of an update is formed from alpha0 (Sec. 3.2 "Parameter Server", Sec. 5.1 Eq. 5). */
+/* How the learning rate of an update is formed from alpha0 (Sec. 3.2 "Parameter Server", Sec. 5.1 Eq. 6). */
 enum rudra_lr_mode {
   RUDRA_LR_CONST = 0,         /* alpha0 * lr_scale (hardsync: lr_scale = sqrt(lambda*mu/B)) */
   RUDRA_LR_STATIC_N = 1,      /* alpha0 * lr_scale / n */
@@ -115,7 +115,7 @@ typedef struct {
   uint64_t hist_len;        /* sigma_max + 1 once a gradient has arrived (see rudra_ps_staleness_hist) */
   uint64_t bytes_absorbed;  /* n_pushes * 4 * P */
   double sigma_mean;        /* sigma_sum / n_pushes */
-  double last_avg_staleness; /* <sigma> of the latest update, Sec. 3.1 Eq. 1 */
+  double last_avg_staleness; /* <sigma> of the latest update, Sec. 3.1 Eq. 2 */
   double theta_sq, theta_inf, v_sq, gbar_sq; /* state after / averaged gradient of the latest update; only with
                                                 RUDRA_FLAG_STATS_NORMS and n_updates > 0 (norms_valid = 1) */
   double kernel_ms;         /* RUDRA_FLAG_TIME_KERNELS: summed device time of the applyUpdate launches ... */
@@ -139,7 +139,7 @@ int rudra_ps_destroy(rudra_ps_t* ps);
 
 /* pushGradient as the server receives it (Sec. 2, Sec. 3.2): one gradient of P floats plus the timestamp of the
  * weights it was computed from.  Computes its staleness, appends ts to the open vector clock and, on the c-th
- * gradient, enqueues sumGradients+applyUpdate (Eq. 2 / Eq. 4 with the rate of the configured mode) and advances
+ * gradient, enqueues sumGradients+applyUpdate (Eq. 3 / Eq. 5 with the rate of the configured mode) and advances
  * the weight timestamp by one.
  *   grad     DEVICE pointer, P contiguous floats, 16-byte aligned.  BORROWED: unless PUSH_ACCUMULATE is set the
  *            buffer must stay allocated and unmodified until the update that consumes it has run; work enqueued
@@ -169,7 +169,7 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out);
 int rudra_ps_staleness_hist(rudra_ps_t* ps, uint64_t* out, uint64_t cap, uint64_t* n_out);
 
 /* Vector clock of update `update_idx` (0-based: the update advancing timestamp update_idx -> update_idx+1): the c
- * gradient timestamps in arrival order, its <sigma> (Eq. 1) and its learning rate.  HOST pointers; avg_sigma_out and
+ * gradient timestamps in arrival order, its <sigma> (Eq. 2) and its learning rate.  HOST pointers; avg_sigma_out and
  * lr_out may be NULL.  ERANGE if the update has not happened, has left the ring, or cap < c. */
 int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out, uint32_t cap, uint32_t* n_out,
                           double* avg_sigma_out, float* lr_out);

@@ -22,6 +22,7 @@ _LIB = os.path.join(_HERE, "librudra_oracle.so")
 
 HARDSYNC, SOFTSYNC = 0, 1
 LR_CONST, LR_STATIC_N, LR_AVG_STALENESS, LR_PER_GRADIENT = 0, 1, 2, 3
+OPT_SGD, OPT_ADAGRAD = 0, 1
 OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM = 0, -1, -2, -3, -4, -5
 
 # every floating-point operation rounded on its own, no value-changing rewrites
@@ -48,7 +49,7 @@ class _Config(C.Structure):
     _fields_ = [("n_params", C.c_uint64), ("n_learners", C.c_uint32), ("n_split", C.c_uint32),
                 ("c_override", C.c_uint32), ("protocol", C.c_int32), ("lr_mode", C.c_int32),
                 ("alpha0", C.c_float), ("lr_scale", C.c_float), ("momentum", C.c_float),
-                ("weight_decay", C.c_float)]
+                ("weight_decay", C.c_float), ("optimizer", C.c_int32), ("adagrad_eps", C.c_float)]
 
 
 class PushResult(C.Structure):
@@ -94,7 +95,7 @@ def _load():
 
 
 def gradients_per_update(n_learners, n_split=1, protocol=SOFTSYNC, c_override=0) -> int:
-    cfg = _Config(1, n_learners, n_split, c_override, protocol, LR_CONST, 0, 1, 0, 0)
+    cfg = _Config(1, n_learners, n_split, c_override, protocol, LR_CONST, 0, 1, 0, 0, OPT_SGD, 0)
     return int(_load().oracle32_gradients_per_update(C.byref(cfg)))
 
 
@@ -110,7 +111,7 @@ class OraclePS:
 
     def __init__(self, init_weights, n_learners, n_split=1, protocol=SOFTSYNC,
                  lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0,
-                 weight_decay=0.0, c_override=0, precision=32):
+                 weight_decay=0.0, c_override=0, precision=32, optimizer=OPT_SGD, adagrad_eps=1e-8):
         lib = _load()
         assert precision in (32, 64)
         self._p = "oracle32_" if precision == 32 else "oracle64_"
@@ -118,7 +119,7 @@ class OraclePS:
         w = np.ascontiguousarray(init_weights, dtype=np.float32)
         self.n_params = int(w.size)
         self.cfg = _Config(self.n_params, n_learners, n_split, c_override, protocol, lr_mode,
-                           alpha0, lr_scale, momentum, weight_decay)
+                           alpha0, lr_scale, momentum, weight_decay, optimizer, adagrad_eps)
         h = C.c_void_p()
         rc = getattr(lib, self._p + "create")(C.byref(self.cfg), w.ctypes.data, C.byref(h))
         if rc != OK:

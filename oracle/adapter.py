@@ -4,11 +4,13 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (HARDSYNC, LR_AVG_STALENESS, LR_CONST, LR_PER_GRADIENT, LR_STATIC_N, SOFTSYNC, OraclePS)
+from . import (HARDSYNC, LR_AVG_STALENESS, LR_CONST, LR_PER_GRADIENT, LR_STATIC_N, OPT_ADAGRAD, OPT_SGD, SOFTSYNC,
+               OraclePS)
 
 PROTOCOL = {"hardsync": HARDSYNC, "softsync": SOFTSYNC}
 LR_MODE = {"const": LR_CONST, "static_n": LR_STATIC_N, "avg_staleness": LR_AVG_STALENESS,
            "per_gradient": LR_PER_GRADIENT}
+OPTIMIZER = {"sgd": OPT_SGD, "adagrad": OPT_ADAGRAD}
 
 
 class OracleServer:
@@ -22,7 +24,8 @@ class OracleServer:
         self.ps = OraclePS(workload.init_weights_at(self.index), workload.n_learners, workload.n_split,
                            PROTOCOL[workload.protocol], LR_MODE[workload.lr_mode], workload.alpha0,
                            workload.lr_scale, workload.momentum, workload.weight_decay, workload.c_override,
-                           precision=precision)
+                           precision=precision, optimizer=OPTIMIZER[workload.optimizer],
+                           adagrad_eps=workload.adagrad_eps)
 
     def push(self, learner, step, ts):
         rc, res = self.ps.push(self.w.grad_at(learner, step, self.index), ts, learner)

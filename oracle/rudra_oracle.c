@@ -25,18 +25,19 @@
  *   staleness      gradient stamped i arriving when the weights are stamped j>=i
  *                  has sigma = j - i (Sec. 3.1 "sigma")
  *   vector clock   the timestamps of the gradients that trigger update i-1 -> i;
- *                  <sigma> = (i-1) - mean(i_1..i_c)  (Sec. 3.1, Eq. 1 "avg staleness")
+ *                  <sigma> = (i-1) - mean(i_1..i_c)  (Sec. 3.1, Eq. 2 "avg staleness")
  *   hardsync       exactly one gradient per learner per step, all lambda averaged,
- *                  staleness always zero (Sec. 3.1, Eq. 2)
+ *                  staleness always zero (Sec. 3.1, Eq. 3)
  *   n-softsync     update after c = floor(lambda/n) gradients, averaged
- *                  (Sec. 3.1, Eq. 4); n = lambda is the async rule (Eq. 3)
+ *                  (Sec. 3.1, Eq. 5); n = lambda is the async rule (Eq. 4)
  *   sumGradients   receive and accumulate (Sec. 2)
  *   applyUpdate    multiply the accumulated gradient by the learning rate and
  *                  update the weights (Sec. 2, Eq. 1c)
  *   learning rate  hardsync: alpha0 times a caller-known factor sqrt(lambda*mu/B);
  *                  softsync: alpha0 times the reciprocal of staleness,
- *                  alpha = alpha0/<sigma> = alpha0/n (Sec. 3.2, Sec. 5.1 Eq. 5)
+ *                  alpha = alpha0/<sigma> = alpha0/n (Sec. 3.2, Sec. 5.1 Eq. 6)
  *   momentum 0.9, weight penalty 5e-4: named, no formula printed (Sec. 4.2).
+ *   AdaGrad: named for the ImageNet 1-softsync runs (Sec. 5.5), no formula or epsilon printed.
  *
  * Readings where the paper is silent (each also listed in the design notes):
  *   - the divisor of the staleness-modulated rate is max(1, <sigma>): the paper's
@@ -52,10 +53,13 @@
  *   - per-gradient modulation (Sec. 5.1 footnote, not explored by the paper):
  *     each arriving gradient is scaled by 1/max(1, sigma_l) before it is added;
  *     the update then uses alpha0*lr_scale.
- *   PARITY UNPINNED BY THE PAPER: the momentum and weight-penalty formulas and the
+ *   - AdaGrad: the cited diagonal rule, h <- h + gbar^2, theta <- theta - alpha*gbar/(sqrt(h)+eps),
+ *     the weight penalty added to gbar first, alpha the staleness-modulated rate, no momentum.
+ *   PARITY UNPINNED BY THE PAPER: the momentum, weight-penalty and AdaGrad formulas and the
  *   per-gradient modulation (no formula is printed); they are pinned only against
- *   a library SGD routine and closed forms.
+ *   library SGD / Adagrad routines and closed forms.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -74,6 +78,7 @@ typedef ORACLE_REAL real;
 
 enum { PROTO_HARDSYNC = 0, PROTO_SOFTSYNC = 1 };
 enum { LR_CONST = 0, LR_STATIC_N = 1, LR_AVG_STALENESS = 2, LR_PER_GRADIENT = 3 };
+enum { OPT_SGD = 0, OPT_ADAGRAD = 1 };
 enum {
   OR_OK = 0,
   OR_EINVAL = -1,
@@ -91,6 +96,8 @@ typedef struct {
   int32_t protocol;
   int32_t lr_mode;
   float alpha0, lr_scale, momentum, weight_decay;
+  int32_t optimizer;   /* OPT_SGD (with optional momentum) or OPT_ADAGRAD */
+  float adagrad_eps;   /* added to sqrt(h) */
 } oracle_config;
 
 typedef struct {
@@ -104,7 +111,7 @@ typedef struct {
 typedef struct {
   oracle_config cfg;
   uint32_t c;
-  real *theta, *vel, *acc;
+  real *theta, *vel, *acc; /* vel: momentum velocity, or AdaGrad's sum of squared gradients h */
   uint64_t ts_cur;
   uint32_t count;
   uint64_t sigma_sum_open; /* sum of sigma over the open clock */
@@ -124,8 +131,8 @@ typedef struct {
 
 static uint32_t gradients_per_update(const oracle_config *cfg) {
   if (cfg->c_override) return cfg->c_override;
-  if (cfg->protocol == PROTO_HARDSYNC) return cfg->n_learners; /* Eq. 2 */
-  return cfg->n_learners / cfg->n_split;                       /* Eq. 4: floor(lambda/n) */
+  if (cfg->protocol == PROTO_HARDSYNC) return cfg->n_learners; /* Eq. 3 */
+  return cfg->n_learners / cfg->n_split;                       /* Eq. 5: floor(lambda/n) */
 }
 
 uint32_t FN(gradients_per_update)(const oracle_config *cfg) { return gradients_per_update(cfg); }
@@ -147,6 +154,8 @@ int FN(create)(const oracle_config *cfg, const float *init_weights, oracle_t **o
   if (cfg->protocol == PROTO_SOFTSYNC && (cfg->n_split < 1 || cfg->n_split > cfg->n_learners))
     return OR_EINVAL;
   if (gradients_per_update(cfg) == 0) return OR_EINVAL;
+  if (cfg->optimizer != OPT_SGD && cfg->optimizer != OPT_ADAGRAD) return OR_EINVAL;
+  if (cfg->optimizer == OPT_ADAGRAD && (cfg->momentum != 0.0f || !(cfg->adagrad_eps >= 0.0f))) return OR_EINVAL;
   oracle_t *o = (oracle_t *)calloc(1, sizeof(oracle_t));
   if (!o) return OR_ENOMEM;
   o->cfg = *cfg;
@@ -210,13 +219,23 @@ static void apply_update(oracle_t *o, real lr) {
   const real wd = (real)o->cfg.weight_decay;
   double gbar_sq = 0.0;
   for (uint64_t k = 0; k < P; ++k) {
-    real gbar = o->acc[k] * inv_c;                 /* Eq. 4: (1/c) * sum */
+    real gbar = o->acc[k] * inv_c;                 /* Eq. 5: (1/c) * sum */
     if (wd != (real)0) {
       real penalty = wd * o->theta[k];             /* L2 weight penalty, Sec. 4.2 */
       gbar = gbar + penalty;
     }
     gbar_sq += (double)gbar * (double)gbar;
-    if (m != (real)0) {                            /* momentum SGD, Sec. 4.2 */
+    if (o->cfg.optimizer == OPT_ADAGRAD) {
+      /* AdaGrad (Duchi, Hazan, Singer 2011, diagonal form; named in Sec. 5.5 for the ImageNet 1-softsync runs):
+       * h <- h + gbar^2 ; theta <- theta - lr * gbar / (sqrt(h) + eps).  h lives in vel[]. */
+      real sq = gbar * gbar;
+      o->vel[k] = o->vel[k] + sq;
+      real root = (sizeof(real) == sizeof(float)) ? (real)sqrtf((float)o->vel[k]) : (real)sqrt((double)o->vel[k]);
+      real denom = root + (real)o->cfg.adagrad_eps;
+      real step = lr * gbar;
+      real scaled = step / denom;
+      o->theta[k] = o->theta[k] - scaled;
+    } else if (m != (real)0) {                     /* momentum SGD, Sec. 4.2 */
       real keep = m * o->vel[k];
       real step = lr * gbar;
       o->vel[k] = keep - step;

@@ -1,7 +1,7 @@
 // Fused sumGradients + applyUpdate kernels of the Rudra parameter server (gfx950 / CDNA4).
 //
 // One launch reads each of the c pushed gradients once, reads and writes theta (and the
-// momentum velocity v) once, and does all of Eq. 4 (average of c gradients) and Eq. 1c
+// momentum velocity v) once, and does all of Eq. 5 (average of c gradients) and Eq. 1c
 // (theta <- theta - alpha * gbar), plus the momentum and weight-penalty terms of Sec. 4.2, in
 // registers.  The path is a pure HBM stream: (c+5) flops per (4c+16) bytes, so there is no
 // MFMA and no LDS staging here; what matters is 128-bit coalesced access, the cache policy of

@@ -1,7 +1,7 @@
 // Host control plane and C ABI of the Rudra parameter-server update path (see include/rudra_ps.h).
 //
 // Everything per message is O(1) integer work on the host (timestamps, staleness, vector
-// clock, trigger: Sec. 3.1; learning rate: Sec. 3.2 / Sec. 5.1 Eq. 5); the only device work is
+// clock, trigger: Sec. 3.1; learning rate: Sec. 3.2 / Sec. 5.1 Eq. 6); the only device work is
 // the fused kernel launch on the c-th gradient.  No data crosses the host-device boundary on
 // the push path and push never waits for the GPU.
 #include "../../include/rudra_ps.h"
@@ -230,7 +230,7 @@ int resolve_timer(rudra_ps* ps, uint64_t launch_idx) {
   return RUDRA_OK;
 }
 
-// sumGradients + applyUpdate for the c pending gradients (Eq. 2 / Eq. 4), one fused launch
+// sumGradients + applyUpdate for the c pending gradients (Eq. 3 / Eq. 5), one fused launch
 // when c <= kMaxFused.
 int enqueue_update(rudra_ps* ps, float lr) {
   const bool weighted = ps->cfg.lr_mode == RUDRA_LR_PER_GRADIENT;
@@ -259,7 +259,7 @@ int enqueue_update(rudra_ps* ps, float lr) {
 
   UpdateArgs a = base_args(ps);
   a.c = n;
-  a.inv_c = 1.0f / (float)ps->c;  // Eq. 4: the mean is over all c gradients of the update
+  a.inv_c = 1.0f / (float)ps->c;  // Eq. 5: the mean is over all c gradients of the update
   a.lr = lr;
   a.reverse = (ps->alternate && (ps->n_updates & 1)) ? 1u : 0u;
   const LaunchShape s = shape_for(ps);
@@ -450,7 +450,7 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
   int applied = 0;
   float lr_used = 0.f;
   if (ps->count == ps->c) {
-    // <sigma> of this update: mean over its clock of (ts_cur - ts_k) = (i-1) - mean(i_k), Eq. 1
+    // <sigma> of this update: mean over its clock of (ts_cur - ts_k) = (i-1) - mean(i_k), Eq. 2
     const double avg_sigma = (double)ps->sigma_sum_open / (double)ps->c;
     double lr = (double)cfg.alpha0 * (double)cfg.lr_scale;
     if (cfg.lr_mode == RUDRA_LR_STATIC_N) lr = lr / (double)cfg.n_split;

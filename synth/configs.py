@@ -33,6 +33,8 @@ class Workload:
     straggler_factor: float = 3.0
     lr_scale: float = 1.0
     c_override: int = 0
+    optimizer: str = "sgd"       # "sgd" (momentum optional) | "adagrad"
+    adagrad_eps: float = 1e-8
 
     @property
     def c(self) -> int:
@@ -81,5 +83,9 @@ C4 = Workload("C4-imagenet-1softsync", 72_000_000, 18, "softsync", 1, "avg_stale
               1e-4, SEED0 + 4, tail_per=100, tail_factor=100.0)
 C5 = Workload("C5-imagenet-lambda-softsync", 72_000_000, 54, "softsync", 54, "avg_staleness", 0.01, 0.9, 5e-4,
               5000, 1e-4, SEED0 + 5)
+
+# The paper's ImageNet 1-softsync runs used AdaGrad instead of momentum SGD (Sec. 5.5)
+C4_ADAGRAD = Workload("C4-imagenet-1softsync-adagrad", 72_000_000, 18, "softsync", 1, "avg_staleness", 0.01, 0.0, 0.0,
+                      3600, 1e-4, SEED0 + 6, tail_per=100, tail_factor=100.0, optimizer="adagrad")
 
 ALL = {"C1": C1, "C2": C2, "C3-n1": C3(1), "C3-n2": C3(2), "C3-n4": C3(4), "C3-n30": C3(30), "C4": C4, "C5": C5}

@@ -31,6 +31,9 @@ MUTANTS = {
     "static_rate_divides_by_c": ("lr = lr / (double)o->cfg.n_split;", "lr = lr / (double)o->c;"),
     "stale_hardsync_accepted": ("if (ts != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; }", ""),
     "average_staleness_uses_sum": ("(double)o->sigma_sum_open / (double)o->c;", "(double)o->sigma_sum_open;"),
+    "adagrad_accumulator_not_summed": ("o->vel[k] = o->vel[k] + sq;", "o->vel[k] = sq;"),
+    "adagrad_eps_inside_the_root": ("real denom = root + (real)o->cfg.adagrad_eps;", "real denom = (real)sqrt((double)o->vel[k] + (double)o->cfg.adagrad_eps);"),
+    "adagrad_penalty_after_accumulator": ("      real sq = gbar * gbar;", "      real sq = (gbar - wd * o->theta[k]) * (gbar - wd * o->theta[k]);"),
     "timestamp_in_clock_is_staleness": ("o->open_clock[o->count] = ts;", "o->open_clock[o->count] = sigma;"),
 }
 

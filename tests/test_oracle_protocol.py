@@ -30,7 +30,7 @@ def test_c_values_printed_by_the_paper():
 def test_c_closed_form(lam):
     for n in range(1, lam + 1):
         assert oracle.gradients_per_update(lam, n) == lam // n
-    assert oracle.gradients_per_update(lam, 1, oracle.HARDSYNC) == lam  # Eq. 2 averages all lambda
+    assert oracle.gradients_per_update(lam, 1, oracle.HARDSYNC) == lam  # Eq. 3 averages all lambda
     assert oracle.gradients_per_update(30, 4) == 7  # floor, not round
     assert oracle.gradients_per_update(30, 4, c_override=8) == 8
 
@@ -105,7 +105,7 @@ def test_staleness_and_clocks_by_brute_force(lam, n):
     assert ps.pending == n_pushes % c                      # leftovers stay pending, unapplied
     assert ps.n_pushes == n_pushes
     # vector clock of update i (advancing ts_{i-1} -> ts_i): the c stamps that triggered it,
-    # all < i, and <sigma> = (i-1) - mean(stamps)   (Eq. 1), as an exact rational
+    # all < i, and <sigma> = (i-1) - mean(stamps)   (Eq. 2), as an exact rational
     clocks, avg = ps.clocks, ps.avg_staleness
     for u in range(ps.n_updates):
         stamps = log["ts_pushed"][u * c:(u + 1) * c]

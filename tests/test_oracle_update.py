@@ -18,7 +18,7 @@ def _rng(seed=0):
 # ---------------------------------------------------------------- hardsync == SGD on the mean gradient
 @pytest.mark.parametrize("momentum,wd", [(0.0, 0.0), (0.9, 0.0), (0.9, 5e-4), (0.0, 5e-4)])
 def test_hardsync_equals_library_sgd_on_the_averaged_gradient(momentum, wd):
-    """Eq. 2 and the mu*lambda = const argument (Sec. 5.3): a hardsync step with lambda learners
+    """Eq. 3 and the mu*lambda = const argument (Sec. 5.3): a hardsync step with lambda learners
     is one SGD step on the mean of their gradients.  torch.optim.SGD (rate outside the velocity,
     dampening 0) is algebraically the same recursion when the rate is constant."""
     rng = _rng(1)
@@ -65,7 +65,7 @@ def test_mu_lambda_equivalence():
 
 # ---------------------------------------------------------------- lambda-softsync == per-gradient (async) updates
 def test_c_equal_one_is_a_loop_of_single_gradient_steps():
-    """n = lambda: the update rule is the Async one (Eq. 3), one step per gradient, here with the
+    """n = lambda: the update rule is the Async one (Eq. 4), one step per gradient, here with the
     rate alpha0/max(1, sigma_i).  Without momentum theta_end = theta_0 - sum_i alpha_i g_i."""
     rng = _rng(3)
     lam, P, n_pushes, a0 = 6, 33, 120, 0.25
@@ -202,7 +202,7 @@ def test_per_gradient_modulation():
 
 
 def test_static_n_rate_and_lr_scale():
-    """alpha = alpha0/n (Eq. 5) and the hardsync factor sqrt(lambda*mu/B) handed in as lr_scale (Sec. 3.2)."""
+    """alpha = alpha0/n (Eq. 6) and the hardsync factor sqrt(lambda*mu/B) handed in as lr_scale (Sec. 3.2)."""
     one = np.ones(1, np.float32)
     ps = OraclePS(np.zeros(1, np.float32), 8, 4, oracle.SOFTSYNC, oracle.LR_STATIC_N, alpha0=1.0, precision=64)
     ps.push(one, 0, 0)
@@ -240,3 +240,69 @@ def test_norms():
     ps.push(np.full(1000, 2.0, np.float32), 1, 0)     # gbar 2, v = -1 - 1 = -2, theta = -2
     n = ps.norms()
     assert n == dict(theta_sq=4000.0, theta_inf=2.0, v_sq=4000.0, gbar_sq=4000.0)
+
+
+# ---------------------------------------------------------------- AdaGrad (named for the ImageNet 1-softsync runs, Sec. 5.5)
+@pytest.mark.parametrize("wd", [0.0, 5e-4])
+def test_adagrad_equals_library_adagrad_on_the_averaged_gradient(wd):
+    """The cited diagonal AdaGrad rule: torch.optim.Adagrad (no rate decay, accumulator from 0) in binary64 on the
+    mean gradient of each hardsync step."""
+    rng = _rng(7)
+    P, lam, steps, lr, eps = 129, 4, 30, 0.05, 1e-6
+    w0 = (0.1 * rng.standard_normal(P)).astype(np.float32)
+    grads = (0.01 * rng.standard_normal((steps, lam, P))).astype(np.float32)
+    kw = dict(alpha0=lr, weight_decay=wd, optimizer=oracle.OPT_ADAGRAD, adagrad_eps=eps)
+    ps64 = OraclePS(w0, lam, 1, oracle.HARDSYNC, oracle.LR_CONST, precision=64, **kw)
+    ps32 = OraclePS(w0, lam, 1, oracle.HARDSYNC, oracle.LR_CONST, precision=32, **kw)
+    p = torch.tensor(w0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adagrad([p], lr=float(np.float32(lr)), weight_decay=float(np.float32(wd)), eps=float(np.float32(eps)),
+                              lr_decay=0.0, initial_accumulator_value=0.0)
+    for s in range(steps):
+        for l in range(lam):
+            ps64.push(grads[s, l], s, l)
+            ps32.push(grads[s, l], s, l)
+        p.grad = torch.tensor(grads[s].astype(np.float64).mean(axis=0))
+        opt.step()
+    ref = p.detach().numpy()
+    assert np.abs(ps64.theta - ref).max() <= 1e-12 * np.abs(ref).max()
+    assert np.abs(ps32.theta.astype(np.float64) - ref).max() <= 2e-6 * np.abs(ref).max()
+    h_ref = opt.state[p]["sum"].numpy()
+    assert np.abs(ps64.velocity - h_ref).max() <= 1e-13 * h_ref.max()       # the accumulator lives in the second state vector
+
+
+def test_adagrad_closed_form_and_staleness_modulated_rate():
+    """Constant gradient g: h_u = u g^2 and theta_u = theta_0 - sum_j alpha_j g / (sqrt(j) |g| + eps); the rate alpha_j is
+    still alpha0 / max(1, sigma_j)."""
+    g, a0, eps = 0.25, 0.5, 1e-3
+    ps = OraclePS(np.zeros(3, np.float32), 4, 4, oracle.SOFTSYNC, oracle.LR_AVG_STALENESS, alpha0=a0,
+                  optimizer=oracle.OPT_ADAGRAD, adagrad_eps=eps, precision=64)
+    stamps = [0, 0, 0, 2, 4, 1, 6]               # staleness 0,1,2,1,0,4,0
+    want = 0.0
+    for j, ts in enumerate(stamps, start=1):
+        rc, r = ps.push(np.full(3, g, np.float32), ts, -1)
+        assert rc == 0 and r.staleness == (j - 1) - ts
+        want -= (a0 / max(1, (j - 1) - ts)) * g / (np.sqrt(j) * g + float(np.float32(eps)))
+    assert abs(ps.theta[0] - want) <= 1e-14
+    assert abs(ps.velocity[0] - len(stamps) * g * g) <= 1e-15
+    with pytest.raises(oracle.OracleError):      # AdaGrad replaces momentum here, it does not combine with it
+        OraclePS(np.zeros(1, np.float32), 1, 1, oracle.HARDSYNC, optimizer=oracle.OPT_ADAGRAD, momentum=0.9)
+
+
+def test_adagrad_binary32_ops_are_rounded_one_by_one():
+    rng = _rng(8)
+    f = np.float32
+    P = 300
+    w0 = rng.standard_normal(P).astype(f)
+    g1, g2 = rng.standard_normal(P).astype(f), rng.standard_normal(P).astype(f)
+    lr, wd, eps = f(0.11), f(5e-4), f(1e-8)
+    ps = OraclePS(w0, 2, 1, oracle.SOFTSYNC, oracle.LR_CONST, alpha0=lr, weight_decay=wd, optimizer=oracle.OPT_ADAGRAD,
+                  adagrad_eps=eps)
+    h, th = np.zeros(P, f), w0.copy()
+    for rep in range(4):
+        ps.push(g1, rep, 0)
+        ps.push(g2, rep, 1)
+        gbar = (g1 + g2) * (f(1) / f(2))
+        gbar = gbar + wd * th
+        h = h + gbar * gbar
+        th = th - (lr * gbar) / (np.sqrt(h) + eps)
+    assert th.dtype == f and np.array_equal(ps.theta, th) and np.array_equal(ps.velocity, h)
