@@ -46,6 +46,14 @@ enum rudra_lr_mode {
                                  summed; the update uses alpha0 * lr_scale */
 };
 
+/* Update rule of applyUpdate. */
+enum rudra_optimizer {
+  RUDRA_OPT_SGD = 0,    /* Eq. 1c, with momentum and weight penalty as configured (Sec. 4.2) */
+  RUDRA_OPT_ADAGRAD = 1 /* the adaptive rule the paper names for its ImageNet 1-softsync runs (Sec. 5.5): h <- h + gbar^2,
+                           theta <- theta - alpha * gbar / (sqrt(h) + adagrad_eps); momentum must be 0; h takes the
+                           place of the velocity (rudra_ps_pull_velocity returns it) */
+};
+
 enum rudra_flags {
   RUDRA_FLAG_STATS_NORMS = 1u,     /* every applyUpdate also reduces ||gbar||^2, ||theta||^2, ||theta||_inf, ||v||^2 */
   RUDRA_FLAG_PUSH_ACCUMULATE = 2u, /* sum each gradient into a server-owned accumulator at push time (the literal
@@ -79,6 +87,8 @@ typedef struct {
   float lr_scale;        /* caller-known factor, e.g. sqrt(lambda*mu/B); use 1 when none */
   float momentum;        /* 0 = plain SGD; else v <- m v - alpha gbar, theta <- theta + v (Sec. 4.2: 0.9) */
   float weight_decay;    /* L2 penalty: gbar <- gbar + wd*theta (Sec. 4.2: 5e-4 on ImageNet) */
+  int32_t optimizer;     /* enum rudra_optimizer */
+  float adagrad_eps;     /* >= 0; only read when optimizer == RUDRA_OPT_ADAGRAD */
   int32_t device;        /* HIP device ordinal */
   uint32_t flags;        /* OR of enum rudra_flags */
   void* stream;          /* hipStream_t, borrowed from the caller (NULL = the device's null stream) */

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_PKG, "lib", "librudra_ps.so")
 
 HARDSYNC, SOFTSYNC = 0, 1
 LR_CONST, LR_STATIC_N, LR_AVG_STALENESS, LR_PER_GRADIENT = 0, 1, 2, 3
+OPT_SGD, OPT_ADAGRAD = 0, 1
 FLAG_STATS_NORMS, FLAG_PUSH_ACCUMULATE, FLAG_CONTROL_ONLY, FLAG_TIME_KERNELS = 1, 2, 4, 8
 OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM, EHIP, ERANGE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
@@ -22,7 +23,7 @@ class Config(C.Structure):
     _fields_ = [("n_params", C.c_uint64), ("n_learners", C.c_uint32), ("n_split", C.c_uint32),
                 ("c_override", C.c_uint32), ("protocol", C.c_int32), ("lr_mode", C.c_int32),
                 ("alpha0", C.c_float), ("lr_scale", C.c_float), ("momentum", C.c_float),
-                ("weight_decay", C.c_float), ("device", C.c_int32), ("flags", C.c_uint32),
+                ("weight_decay", C.c_float), ("optimizer", C.c_int32), ("adagrad_eps", C.c_float), ("device", C.c_int32), ("flags", C.c_uint32),
                 ("stream", C.c_void_p), ("clock_ring", C.c_uint32), ("launch_block", C.c_uint32),
                 ("launch_unroll", C.c_uint32), ("launch_vec", C.c_uint32), ("launch_grid", C.c_uint32),
                 ("launch_waves_per_cu", C.c_uint32), ("launch_alternate", C.c_uint32)]
@@ -94,10 +95,11 @@ class ParameterServer:
     def __init__(self, n_params, n_learners, init_weights_ptr=0, n_split=1, protocol=SOFTSYNC,
                  lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0, weight_decay=0.0,
                  c_override=0, device=0, stream=0, flags=0, clock_ring=0, launch_block=0, launch_unroll=0,
-                 launch_vec=0, launch_grid=0, launch_waves_per_cu=0, launch_alternate=0):
+                 launch_vec=0, launch_grid=0, launch_waves_per_cu=0, launch_alternate=0, optimizer=OPT_SGD,
+                 adagrad_eps=1e-8):
         self._L = lib()
         self.cfg = Config(n_params, n_learners, n_split, c_override, protocol, lr_mode, alpha0, lr_scale, momentum,
-                          weight_decay, device, flags, stream or None, clock_ring, launch_block, launch_unroll,
+                          weight_decay, optimizer, adagrad_eps, device, flags, stream or None, clock_ring, launch_block, launch_unroll,
                           launch_vec, launch_grid, launch_waves_per_cu, launch_alternate)
         h = C.c_void_p()
         rc = self._L.rudra_ps_create(C.byref(self.cfg), init_weights_ptr or None, C.byref(h))

@@ -12,6 +12,8 @@
 //          per-gradient-staleness mode, Sec. 5.1 footnote; otherwise no multiply at all)
 //   gbar = s * inv_c;            if wd != 0: gbar = gbar + wd*theta[k]
 //   momentum:  v[k] = m*v[k] - lr*gbar ; theta[k] = theta[k] + v[k]
+//   AdaGrad:   h[k] = h[k] + gbar*gbar ; theta[k] = theta[k] - (lr*gbar) / (sqrt(h[k]) + eps)
+//              (h shares the second state vector with v; sqrt and divide correctly rounded)
 //   otherwise: theta[k] = theta[k] - lr*gbar
 // every operation rounded on its own: this file is compiled with -ffp-contract=off and the
 // pragma below, so no multiply-add is ever fused.
@@ -43,8 +45,10 @@ struct UpdateArgs {
   uint64_t ntiles;   // ceil((n_params/4) / (blockDim*V)), computed on the host
   uint32_t c;        // gradients in this launch, 1..kMaxFused
   uint32_t reverse;  // 1: walk the tiles from the last to the first
-  float inv_c, lr, momentum, weight_decay;
+  float inv_c, lr, momentum, weight_decay, adagrad_eps;
 };
+
+enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second state vector, if any
 
 // Cache policy (measured on MI355X at 72M parameters, c = 18 and c = 1):
 //   gradients   read once, never again: non-temporal loads (+4 %).
@@ -115,18 +119,27 @@ struct Norms {
 };
 
 // applyUpdate on one element.  The single place where the update rule is written.
-template <bool MOMENTUM, bool DECAY, bool STATS>
+template <int OPT, bool DECAY, bool STATS>
 __device__ __forceinline__ void update_element(float s, float& th, float& v, const UpdateArgs& a, Norms& n) {
   float gbar = s * a.inv_c;
   if (DECAY) {
     float penalty = a.weight_decay * th;
     gbar = gbar + penalty;
   }
-  if (MOMENTUM) {
+  if (OPT == kOptMomentum) {
     float keep = a.momentum * v;
     float step = a.lr * gbar;
     v = keep - step;
     th = th + v;
+  } else if (OPT == kOptAdagrad) {
+    float sq = gbar * gbar;
+    v = v + sq;
+    // __builtin_sqrtf and '/' compile to the correctly rounded sequences (v_sqrt_f32 plus the +-1 ulp fix-up;
+    // v_div_scale/fmas/fixup); the __fsqrt_rn device function does not (bare v_sqrt_f32, 1 ulp)
+    float denom = __builtin_sqrtf(v) + a.adagrad_eps;
+    float step = a.lr * gbar;
+    float scaled = step / denom;
+    th = th - scaled;
   } else {
     float step = a.lr * gbar;
     th = th - step;
@@ -134,19 +147,19 @@ __device__ __forceinline__ void update_element(float s, float& th, float& v, con
   if (STATS) {
     n.gbar_sq += gbar * gbar;
     n.theta_sq += th * th;
-    if (MOMENTUM) n.v_sq += v * v;
+    if (OPT != kOptSgd) n.v_sq += v * v;
     n.theta_inf = fmaxf(n.theta_inf, fabsf(th));
   }
 }
 
-template <bool MOMENTUM, bool DECAY, bool STATS>
+template <int OPT, bool DECAY, bool STATS>
 __device__ __forceinline__ void update_vec4(const floatx4& s, floatx4& th, floatx4& ve, const UpdateArgs& a, Norms& n) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    float t = th[i], v = MOMENTUM ? ve[i] : 0.f;
-    update_element<MOMENTUM, DECAY, STATS>(s[i], t, v, a, n);
+    float t = th[i], v = (OPT != kOptSgd) ? ve[i] : 0.f;
+    update_element<OPT, DECAY, STATS>(s[i], t, v, a, n);
     th[i] = t;
-    if (MOMENTUM) ve[i] = v;
+    if (OPT != kOptSgd) ve[i] = v;
   }
 }
 
@@ -190,7 +203,7 @@ __device__ __forceinline__ void block_reduce_norms(const Norms& n, double* parti
 // the c+2 streams.  Workgroups take tiles blockIdx, blockIdx+gridDim, ... (grid-stride); the
 // host normally launches one workgroup per tile.  The last P%4 elements are done by the first
 // lanes of workgroup 0 with scalar accesses.
-template <bool MOMENTUM, bool DECAY, bool WEIGHTED, bool STATS, int U, int V>
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int U, int V>
 __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t tile = (uint64_t)blockDim.x * V;
@@ -210,25 +223,25 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         th[v] = load_state4(theta4, iv[v]);
-        if (MOMENTUM) ve[v] = load_state4(vel4, iv[v]);
+        if (OPT != kOptSgd) ve[v] = load_state4(vel4, iv[v]);
       }
       sum_gradients<WEIGHTED, U, V>(gs, a.c, iv, s);
 #pragma unroll
       for (int v = 0; v < V; ++v) {
-        update_vec4<MOMENTUM, DECAY, STATS>(s[v], th[v], ve[v], a, n);
+        update_vec4<OPT, DECAY, STATS>(s[v], th[v], ve[v], a, n);
         store_state4(theta4, iv[v], th[v]);
-        if (MOMENTUM) store_state4(vel4, iv[v], ve[v]);
+        if (OPT != kOptSgd) store_state4(vel4, iv[v], ve[v]);
       }
     } else {
       for (int v = 0; v < V; ++v) {
         const uint64_t i1[1] = {base + (uint64_t)v * blockDim.x};
         if (i1[0] >= n4) break;
         floatx4 th = load_state4(theta4, i1[0]), ve = {0.f, 0.f, 0.f, 0.f}, s[1];
-        if (MOMENTUM) ve = load_state4(vel4, i1[0]);
+        if (OPT != kOptSgd) ve = load_state4(vel4, i1[0]);
         sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
-        update_vec4<MOMENTUM, DECAY, STATS>(s[0], th, ve, a, n);
+        update_vec4<OPT, DECAY, STATS>(s[0], th, ve, a, n);
         store_state4(theta4, i1[0], th);
-        if (MOMENTUM) store_state4(vel4, i1[0], ve);
+        if (OPT != kOptSgd) store_state4(vel4, i1[0], ve);
       }
     }
   }
@@ -236,10 +249,10 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
     const uint64_t k = (n4 << 2) + threadIdx.x;
     if (k < a.n_params) {
       float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
-      float th = a.theta[k], ve = MOMENTUM ? a.vel[k] : 0.f;
-      update_element<MOMENTUM, DECAY, STATS>(s, th, ve, a, n);
+      float th = a.theta[k], ve = (OPT != kOptSgd) ? a.vel[k] : 0.f;
+      update_element<OPT, DECAY, STATS>(s, th, ve, a, n);
       a.theta[k] = th;
-      if (MOMENTUM) a.vel[k] = ve;
+      if (OPT != kOptSgd) a.vel[k] = ve;
     }
   }
   if (STATS) block_reduce_norms(n, a.partials);

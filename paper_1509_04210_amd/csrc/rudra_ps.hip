@@ -98,6 +98,11 @@ int hip_fail(rudra_ps* ps, hipError_t e) {
     if (e_ != hipSuccess) return hip_fail(ps, e_); \
   } while (0)
 
+int kernel_optimizer(const rudra_ps_config_t& cfg) {
+  if (cfg.optimizer == RUDRA_OPT_ADAGRAD) return rudra::kOptAdagrad;
+  return cfg.momentum != 0.0f ? rudra::kOptMomentum : rudra::kOptSgd;
+}
+
 uint32_t gradients_per_update(const rudra_ps_config_t& cfg) {
   if (cfg.c_override) return cfg.c_override;
   if (cfg.protocol == RUDRA_HARDSYNC) return cfg.n_learners;
@@ -133,43 +138,47 @@ LaunchShape shape_for(const rudra_ps* ps) {
   return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(ps->waves_per_cu, ps->block)};
 }
 
-// ---- kernel dispatch: runtime (momentum, decay, weighted, stats, unroll, vec) -> template instance ----
-template <bool MOM, bool WD, bool W, bool ST, int U>
+// ---- kernel dispatch: runtime (optimizer, decay, weighted, stats, unroll, vec) -> template instance ----
+template <int OPT, bool WD, bool W, bool ST, int U>
 void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (vec) {
-    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
-    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
-    default: hipLaunchKernelGGL((rudra::apply_update_kernel<MOM, WD, W, ST, U, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
+    case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
+    case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
+    default: hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, U, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
   }
 }
-template <bool MOM, bool WD, bool W, bool ST>
+template <int OPT, bool WD, bool W, bool ST>
 void launch_apply_u(uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (unroll) {
-    case 1: launch_apply_v<MOM, WD, W, ST, 1>(vec, s, st, gs, a); break;
-    case 2: launch_apply_v<MOM, WD, W, ST, 2>(vec, s, st, gs, a); break;
-    case 4: launch_apply_v<MOM, WD, W, ST, 4>(vec, s, st, gs, a); break;
-    default: launch_apply_v<MOM, WD, W, ST, 8>(vec, s, st, gs, a); break;
+    case 1: launch_apply_v<OPT, WD, W, ST, 1>(vec, s, st, gs, a); break;
+    case 2: launch_apply_v<OPT, WD, W, ST, 2>(vec, s, st, gs, a); break;
+    case 4: launch_apply_v<OPT, WD, W, ST, 4>(vec, s, st, gs, a); break;
+    default: launch_apply_v<OPT, WD, W, ST, 8>(vec, s, st, gs, a); break;
   }
 }
-template <bool MOM, bool WD>
+template <int OPT, bool WD>
 void launch_apply_ws(bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
                      const GradSet& gs, const UpdateArgs& a) {
   if (weighted) {
-    if (stats) launch_apply_u<MOM, WD, true, true>(unroll, vec, s, st, gs, a);
-    else launch_apply_u<MOM, WD, true, false>(unroll, vec, s, st, gs, a);
+    if (stats) launch_apply_u<OPT, WD, true, true>(unroll, vec, s, st, gs, a);
+    else launch_apply_u<OPT, WD, true, false>(unroll, vec, s, st, gs, a);
   } else {
-    if (stats) launch_apply_u<MOM, WD, false, true>(unroll, vec, s, st, gs, a);
-    else launch_apply_u<MOM, WD, false, false>(unroll, vec, s, st, gs, a);
+    if (stats) launch_apply_u<OPT, WD, false, true>(unroll, vec, s, st, gs, a);
+    else launch_apply_u<OPT, WD, false, false>(unroll, vec, s, st, gs, a);
   }
 }
-void launch_apply(bool mom, bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s,
+template <int OPT>
+void launch_apply_d(bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
+                    const GradSet& gs, const UpdateArgs& a) {
+  if (decay) launch_apply_ws<OPT, true>(weighted, stats, unroll, vec, s, st, gs, a);
+  else launch_apply_ws<OPT, false>(weighted, stats, unroll, vec, s, st, gs, a);
+}
+void launch_apply(int opt, bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s,
                   hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
-  if (mom) {
-    if (decay) launch_apply_ws<true, true>(weighted, stats, unroll, vec, s, st, gs, a);
-    else launch_apply_ws<true, false>(weighted, stats, unroll, vec, s, st, gs, a);
-  } else {
-    if (decay) launch_apply_ws<false, true>(weighted, stats, unroll, vec, s, st, gs, a);
-    else launch_apply_ws<false, false>(weighted, stats, unroll, vec, s, st, gs, a);
+  switch (opt) {
+    case rudra::kOptMomentum: launch_apply_d<rudra::kOptMomentum>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
+    case rudra::kOptAdagrad: launch_apply_d<rudra::kOptAdagrad>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
+    default: launch_apply_d<rudra::kOptSgd>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
   }
 }
 void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
@@ -195,6 +204,7 @@ UpdateArgs base_args(const rudra_ps* ps) {
   a.n_params = ps->cfg.n_params;
   a.momentum = ps->cfg.momentum;
   a.weight_decay = ps->cfg.weight_decay;
+  a.adagrad_eps = ps->cfg.adagrad_eps;
   return a;
 }
 
@@ -273,7 +283,7 @@ int enqueue_update(rudra_ps* ps, float lr) {
     slot = (uint32_t)(ps->timed_launches % kTimerRing);
     RUDRA_HIP(ps, hipEventRecord(ps->ev_start[slot], ps->stream));
   }
-  launch_apply(ps->cfg.momentum != 0.0f, ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
+  launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
   RUDRA_HIP(ps, hipGetLastError());
   if (ps->time_kernels) {
     RUDRA_HIP(ps, hipEventRecord(ps->ev_stop[slot], ps->stream));
@@ -296,6 +306,8 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->lr_mode < RUDRA_LR_CONST || c->lr_mode > RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;
   if (c->protocol == RUDRA_SOFTSYNC && (c->n_split < 1 || c->n_split > c->n_learners)) return RUDRA_EINVAL;
   if (gradients_per_update(*c) == 0) return RUDRA_EINVAL;
+  if (c->optimizer != RUDRA_OPT_SGD && c->optimizer != RUDRA_OPT_ADAGRAD) return RUDRA_EINVAL;
+  if (c->optimizer == RUDRA_OPT_ADAGRAD && (c->momentum != 0.0f || !(c->adagrad_eps >= 0.0f))) return RUDRA_EINVAL;
   if (c->launch_block && (c->launch_block < 64 || c->launch_block > 1024 || c->launch_block % 64)) return RUDRA_EINVAL;
   if (c->launch_unroll && c->launch_unroll != 1 && c->launch_unroll != 2 && c->launch_unroll != 4 && c->launch_unroll != 8)
     return RUDRA_EINVAL;
@@ -358,7 +370,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   } else {
     // about kInFlightKiBPerCu KiB of loads in flight per CU: each resident wave has theta, v and up to `unroll`
     // gradient loads (1 KiB each) outstanding
-    const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (config->momentum != 0.0f ? 1u : 0u);
+    const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (kernel_optimizer(*config) != rudra::kOptSgd ? 1u : 0u);
     const uint32_t waves_per_wg = ps->block / 64;
     uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
     w = std::max(w, std::max(4u, waves_per_wg));

@@ -15,6 +15,7 @@ from . import binding as B
 PROTOCOL = {"hardsync": B.HARDSYNC, "softsync": B.SOFTSYNC}
 LR_MODE = {"const": B.LR_CONST, "static_n": B.LR_STATIC_N, "avg_staleness": B.LR_AVG_STALENESS,
            "per_gradient": B.LR_PER_GRADIENT}
+OPTIMIZER = {"sgd": B.OPT_SGD, "adagrad": B.OPT_ADAGRAD}
 
 
 class HipServer:
@@ -41,7 +42,8 @@ class HipServer:
         self.ps = B.ParameterServer(P, workload.n_learners, init.data_ptr(), workload.n_split,
                                     PROTOCOL[workload.protocol], LR_MODE[workload.lr_mode], workload.alpha0,
                                     workload.lr_scale, workload.momentum, workload.weight_decay,
-                                    workload.c_override, device, self.sh, flags, **launch)
+                                    workload.c_override, device, self.sh, flags, optimizer=OPTIMIZER[workload.optimizer],
+                                    adagrad_eps=workload.adagrad_eps, **launch)
         self.pregenerated = pregenerated
         for i in range(pregenerated):
             self._fill(self.ring[i], i % workload.n_learners, i // workload.n_learners)

@@ -58,7 +58,10 @@ def test_strerror_and_null_arguments():
     for bad in (dict(n_params=0, n_learners=1), dict(n_params=1, n_learners=0), dict(n_params=1, n_learners=3, n_split=4),
                 dict(n_params=1, n_learners=3, n_split=0), dict(n_params=1, n_learners=3, launch_block=100),
                 dict(n_params=1, n_learners=3, launch_unroll=3), dict(n_params=1, n_learners=3, launch_unroll=8, launch_vec=4),
-                dict(n_params=1, n_learners=3, flags=1 << 20), dict(n_params=1, n_learners=3, alpha0=float("nan"))):
+                dict(n_params=1, n_learners=3, flags=1 << 20), dict(n_params=1, n_learners=3, optimizer=2),
+                dict(n_params=1, n_learners=3, optimizer=B.OPT_ADAGRAD, momentum=0.9),
+                dict(n_params=1, n_learners=3, optimizer=B.OPT_ADAGRAD, adagrad_eps=-1.0), dict(n_params=1, n_learners=3, launch_alternate=3),
+                dict(n_params=1, n_learners=3, launch_waves_per_cu=1), dict(n_params=1, n_learners=3, alpha0=float("nan"))):
         with pytest.raises(R.RudraError) as e:
             R.ParameterServer(flags=bad.pop("flags", B.FLAG_CONTROL_ONLY), **bad)
         assert e.value.status == B.EINVAL
@@ -88,7 +91,8 @@ class _Control:
     def __init__(self, w, **kw):
         self.ps = R.ParameterServer(w.n_params, w.n_learners, 0, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode],
                                     w.alpha0, w.lr_scale, w.momentum, w.weight_decay, w.c_override,
-                                    flags=B.FLAG_CONTROL_ONLY, **kw)
+                                    flags=B.FLAG_CONTROL_ONLY, optimizer=B.OPT_ADAGRAD if w.optimizer == "adagrad" else B.OPT_SGD,
+                                    adagrad_eps=w.adagrad_eps, **kw)
 
     def push(self, l, s, ts):
         rc, r = self.ps.push_gradient(0, ts, l)
@@ -104,7 +108,8 @@ class _OracleControl:
     def __init__(self, w):
         self.ps = OraclePS(np.zeros(1, np.float32), w.n_learners, w.n_split, oracle.HARDSYNC if w.protocol == "hardsync" else oracle.SOFTSYNC,
                            {"const": 0, "static_n": 1, "avg_staleness": 2, "per_gradient": 3}[w.lr_mode], w.alpha0,
-                           w.lr_scale, w.momentum, w.weight_decay, w.c_override)
+                           w.lr_scale, w.momentum, w.weight_decay, w.c_override,
+                           optimizer=oracle.OPT_ADAGRAD if w.optimizer == "adagrad" else oracle.OPT_SGD)
         self.g = np.zeros(1, np.float32)
 
     def push(self, l, s, ts):

@@ -34,7 +34,7 @@ def _compare(hip, ora, w, check_bits=True):
     scale = np.abs(ref).max()
     err = np.abs(th.astype(np.float64) - ref.astype(np.float64)).max()
     assert err <= TOL * scale, f"theta: max abs err {err:.3e} vs {TOL * scale:.3e}"
-    if w.momentum != 0:
+    if w.momentum != 0 or w.optimizer == "adagrad":
         ve = hip.velocity().cpu().numpy()
         vref = ora.ps.velocity
         verr = np.abs(ve.astype(np.float64) - vref.astype(np.float64)).max()
@@ -90,6 +90,7 @@ SMALL = {
     "C3-n30": (configs.C3(30), 50_005, 600),
     "C4": (configs.C4, 90_007, 360),                 # c = 18, heavy-tailed gradients, momentum
     "C5": (configs.C5, 90_001, 700),                 # c = 1, momentum + weight penalty, staleness up to ~100
+    "C4-adagrad": (configs.C4_ADAGRAD, 90_003, 360),  # AdaGrad instead of momentum
 }
 
 
@@ -139,6 +140,20 @@ def test_rate_modes(hipmod, lr_mode, momentum, wd):
     w = _with(configs.C3(4).scaled(n_params=20_002, n_pushes=350), lr_mode=lr_mode, momentum=momentum,
               weight_decay=wd, alpha0=0.05)
     hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+@pytest.mark.parametrize("lr_mode,wd,eps", [("avg_staleness", 0.0, 1e-8), ("avg_staleness", 5e-4, 1e-3),
+                                            ("per_gradient", 5e-4, 1e-8), ("const", 0.0, 0.0)])
+def test_adagrad_modes(hipmod, lr_mode, wd, eps):
+    """AdaGrad: sqrt and divide are correctly rounded on both sides, so the accumulator h and theta are bit-identical."""
+    w = _with(configs.C3(4).scaled(n_params=30_003, n_pushes=420), optimizer="adagrad", adagrad_eps=eps, lr_mode=lr_mode,
+              weight_decay=wd, alpha0=0.05)
+    hip, ora = _run_both(hipmod, w, launch_unroll=2, launch_vec=2)
+    th, h = hip.weights().cpu().numpy(), hip.velocity().cpu().numpy()
+    assert np.abs(th.astype(np.float64) - ora.ps.theta).max() <= TOL * np.abs(ora.ps.theta).max()
+    assert np.array_equal(th, ora.ps.theta) and np.array_equal(h, ora.ps.velocity)
     _compare(hip, ora, w)
     hip.close()
 
@@ -241,7 +256,7 @@ def _sample_indices(P, seed, n_random, span=4096):
     return np.unique(np.concatenate([head, tail, rand])).astype(np.uint64)
 
 
-FULL = {"C2": 3000, "C3-n1": 16384, "C3-n2": 16384, "C3-n4": 16384, "C3-n30": 16384, "C4": 16384, "C5": 16384}
+FULL = {"C4-adagrad": 16384, "C2": 3000, "C3-n1": 16384, "C3-n2": 16384, "C3-n4": 16384, "C3-n30": 16384, "C4": 16384, "C5": 16384}
 
 
 @pytest.mark.parametrize("name", list(FULL))
@@ -264,7 +279,7 @@ def test_full_size_full_length_parity_on_sampled_elements(hipmod, name):
     ref = ora.ps.theta
     assert np.abs(th.astype(np.float64) - ref).max() <= TOL * np.abs(ref).max()
     assert np.array_equal(th, ref)
-    if w.momentum != 0:
+    if w.momentum != 0 or w.optimizer == "adagrad":
         ve = hip.velocity()[sel].cpu().numpy()
         vref = ora.ps.velocity
         assert np.abs(ve.astype(np.float64) - vref).max() <= TOL * np.abs(vref).max()
