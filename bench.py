@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--vec", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--double-buffer", action="store_true", help="run the server with RUDRA_FLAG_DOUBLE_BUFFER")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
     ap.add_argument("--calibration-copies", type=int, default=0,
@@ -154,7 +155,8 @@ def main():
 
     launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid)
     w = configs.ALL[args.workload]
-    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, **launch)
+    base_flags = B.FLAG_DOUBLE_BUFFER if args.double_buffer else 0
+    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, **launch)
     bytes_upd = algorithmic_bytes_per_update(w)
     ups = r["updates"] / r["wall_s"]
     kernel_ms = r["event_ms"] / r["updates"]     # the timed region is back-to-back applyUpdate launches only
@@ -167,7 +169,8 @@ def main():
         "config": {"workload": f"{w.name}: P={w.n_params} fp32, lambda={w.n_learners}, {w.n_split}-softsync (c={w.c}), "
                                f"momentum={w.momentum}, wd={w.weight_decay}, lr=alpha0/max(1,<sigma>), "
                                f"ring of {max(args.ring, w.c + 1)} pre-generated gradients",
-                   "pushes_per_step": w.c, "launch": {k: v for k, v in launch.items() if v}},
+                   "pushes_per_step": w.c, "launch": {k: v for k, v in launch.items() if v},
+                   "double_buffer": bool(args.double_buffer)},
         "absorbed_gradient_GBps": r["pushes"] * 4 * w.n_params / r["wall_s"] / 1e9,
         "pushes_per_s": r["pushes"] / r["wall_s"],
         "mean_staleness": r["sigma_mean"],
@@ -184,7 +187,7 @@ def main():
         del src, dst
     if not args.no_extra:
         # per-launch HIP events around every applyUpdate (library flag), same workload
-        rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=B.FLAG_TIME_KERNELS, **launch)
+        rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=base_flags | B.FLAG_TIME_KERNELS, **launch)
         k_ms = rt["kernel_ms"] / max(1, rt["kernel_launches"])
         line["roofline"]["per_launch_event_ms"] = k_ms
         line["roofline"]["per_launch_event_GBps"] = bytes_upd / (k_ms * 1e-3) / 1e9
@@ -192,7 +195,7 @@ def main():
         # weight penalty) and the 1-softsync case under AdaGrad (what the paper ran for ImageNet 1-softsync, Sec. 5.5)
         line["extra"] = {}
         for other in ([configs.C5] if args.workload == "C4" else [configs.C4]) + [configs.C4_ADAGRAD]:
-            ro = run_gpu(other, 1000 if other.c == 1 else 200, 10, ring=args.ring, **launch)
+            ro = run_gpu(other, 1000 if other.c == 1 else 200, 10, ring=args.ring, flags=base_flags, **launch)
             bo = algorithmic_bytes_per_update(other)
             o_ms = ro["event_ms"] / ro["updates"]
             line["extra"][other.name] = {

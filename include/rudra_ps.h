@@ -61,7 +61,11 @@ enum rudra_flags {
                                       soon as work it enqueues later on the stream runs.  Same bits as the default. */
   RUDRA_FLAG_CONTROL_ONLY = 4u,    /* timestamps, staleness, clocks and rates only: no device memory, no kernels;
                                       grad may be NULL; pulling weights is an error.  For host-side tests. */
-  RUDRA_FLAG_TIME_KERNELS = 8u     /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t */
+  RUDRA_FLAG_TIME_KERNELS = 8u,    /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t */
+  RUDRA_FLAG_DOUBLE_BUFFER = 16u   /* keep two weight buffers: update i reads one and writes the other (no extra traffic),
+                                      so the weights of timestamp ts stay readable while update ts+1 runs: the
+                                      computation-buffer / communication-buffer pair with a pointer swap of Sec. 3.3,
+                                      on the server side.  See rudra_ps_weights_view.  Costs 4P bytes of HBM. */
 };
 
 enum rudra_status {
@@ -136,6 +140,10 @@ typedef struct {
   int32_t norms_valid;
   int32_t last_hip_error;   /* hipError_t of the latest failed HIP call, 0 if none */
   uint32_t reserved;
+  uint64_t n_weight_copies; /* rudra_ps_pull_weights calls that copied the weights ... */
+  uint64_t n_ts_inquiries;  /* ... and those that only asked for the timestamp (Sec. 3.2 "Learner": a learner asks first
+                               and skips the transfer when nothing changed) */
+  uint64_t n_weight_views;  /* rudra_ps_weights_view calls */
 } rudra_ps_stats_t;
 
 /* Create a server.  init_weights: DEVICE pointer to P floats, copied (the caller keeps its buffer); in
@@ -165,6 +173,13 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
  * receiving a copy enqueued on the stream after all updates so far, or NULL for the timestamp inquiry a learner
  * makes first to skip the transfer.  ts_out: HOST pointer, may be NULL. */
 int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out);
+
+/* Zero-copy pullWeights: a DEVICE pointer to the P weights of the current timestamp (HOST pointers theta_out, ts_out
+ * receive it and the timestamp).  The weights are produced by work already enqueued on the server's stream: read them
+ * on that stream, or after an event recorded on it.  With RUDRA_FLAG_DOUBLE_BUFFER the contents stay unchanged until the
+ * SECOND update after this call is enqueued (the next update only reads this buffer); without it, only until the next
+ * update is enqueued.  Read-only for the caller. */
+int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_out);
 
 /* Copy of the momentum velocity v (DEVICE pointer to P floats), enqueued on the stream. */
 int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst);

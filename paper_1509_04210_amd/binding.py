@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_PKG, "lib", "librudra_ps.so")
 HARDSYNC, SOFTSYNC = 0, 1
 LR_CONST, LR_STATIC_N, LR_AVG_STALENESS, LR_PER_GRADIENT = 0, 1, 2, 3
 OPT_SGD, OPT_ADAGRAD = 0, 1
-FLAG_STATS_NORMS, FLAG_PUSH_ACCUMULATE, FLAG_CONTROL_ONLY, FLAG_TIME_KERNELS = 1, 2, 4, 8
+FLAG_STATS_NORMS, FLAG_PUSH_ACCUMULATE, FLAG_CONTROL_ONLY, FLAG_TIME_KERNELS, FLAG_DOUBLE_BUFFER = 1, 2, 4, 8, 16
 OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM, EHIP, ERANGE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 
@@ -42,7 +42,8 @@ class Stats(C.Structure):
                 ("v_sq", C.c_double), ("gbar_sq", C.c_double), ("kernel_ms", C.c_double),
                 ("kernel_launches", C.c_uint64), ("pending", C.c_uint32), ("c", C.c_uint32),
                 ("last_lr", C.c_float), ("norms_valid", C.c_int32), ("last_hip_error", C.c_int32),
-                ("reserved", C.c_uint32)]
+                ("reserved", C.c_uint32), ("n_weight_copies", C.c_uint64), ("n_ts_inquiries", C.c_uint64),
+                ("n_weight_views", C.c_uint64)]
 
 
 _lib = None
@@ -62,6 +63,7 @@ def lib():
             "rudra_ps_destroy": [vp],
             "rudra_ps_push_gradient": [vp, vp, u64, i32, C.POINTER(PushResult)],
             "rudra_ps_pull_weights": [vp, vp, C.POINTER(u64)],
+            "rudra_ps_weights_view": [vp, C.POINTER(vp), C.POINTER(u64)],
             "rudra_ps_pull_velocity": [vp, vp],
             "rudra_ps_stats": [vp, C.POINTER(Stats)],
             "rudra_ps_staleness_hist": [vp, C.POINTER(u64), u64, C.POINTER(u64)],
@@ -128,6 +130,14 @@ class ParameterServer:
         if rc != OK:
             raise RudraError(rc, "rudra_ps_pull_weights")
         return ts.value
+
+    def weights_view(self):
+        """(device address of the current weights, their timestamp): zero-copy pullWeights."""
+        p, ts = C.c_void_p(), C.c_uint64()
+        rc = self._L.rudra_ps_weights_view(self._h, C.byref(p), C.byref(ts))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_weights_view")
+        return p.value, ts.value
 
     def pull_velocity(self, dst_ptr):
         rc = self._L.rudra_ps_pull_velocity(self._h, dst_ptr)

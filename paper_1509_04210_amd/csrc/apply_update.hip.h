@@ -37,7 +37,8 @@ struct GradSet {
 };
 
 struct UpdateArgs {
-  float* theta;
+  const float* theta;  // weights before the update ...
+  float* theta_out;    // ... and where the updated weights go: the same buffer, or the other half of a double buffer
   float* vel;
   float* sum_out;    // sum kernel only: where the running sum goes (may alias p[0])
   double* partials;  // STATS: kNumNorms doubles per workgroup
@@ -208,8 +209,9 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t tile = (uint64_t)blockDim.x * V;
   const uint64_t ntiles = a.ntiles;
-  floatx4* __restrict__ theta4 = reinterpret_cast<floatx4*>(a.theta);
-  floatx4* __restrict__ vel4 = reinterpret_cast<floatx4*>(a.vel);
+  const floatx4* theta4 = reinterpret_cast<const floatx4*>(a.theta);  // may alias theta_out4: each position is
+  floatx4* theta_out4 = reinterpret_cast<floatx4*>(a.theta_out);     // read, then written, by one lane
+  floatx4* vel4 = reinterpret_cast<floatx4*>(a.vel);
   Norms n = {0.f, 0.f, 0.f, 0.f};
 
   for (uint64_t t0 = blockIdx.x; t0 < ntiles; t0 += gridDim.x) {
@@ -229,7 +231,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         update_vec4<OPT, DECAY, STATS>(s[v], th[v], ve[v], a, n);
-        store_state4(theta4, iv[v], th[v]);
+        store_state4(theta_out4, iv[v], th[v]);
         if (OPT != kOptSgd) store_state4(vel4, iv[v], ve[v]);
       }
     } else {
@@ -240,7 +242,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
         if (OPT != kOptSgd) ve = load_state4(vel4, i1[0]);
         sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
         update_vec4<OPT, DECAY, STATS>(s[0], th, ve, a, n);
-        store_state4(theta4, i1[0], th);
+        store_state4(theta_out4, i1[0], th);
         if (OPT != kOptSgd) store_state4(vel4, i1[0], ve);
       }
     }
@@ -251,7 +253,7 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
       float th = a.theta[k], ve = (OPT != kOptSgd) ? a.vel[k] : 0.f;
       update_element<OPT, DECAY, STATS>(s, th, ve, a, n);
-      a.theta[k] = th;
+      a.theta_out[k] = th;
       if (OPT != kOptSgd) a.vel[k] = ve;
     }
   }

@@ -47,7 +47,9 @@ struct rudra_ps {
   int last_hip_error = 0;
 
   // device state (owned)
-  float* theta = nullptr;
+  float* theta2[2] = {nullptr, nullptr};  // [1] only with DOUBLE_BUFFER
+  uint32_t cur = 0;                        // which of them holds the weights of ts_cur
+  bool double_buffer = false;
   float* vel = nullptr;
   float* acc = nullptr;        // running sum: PUSH_ACCUMULATE, or folding more than kMaxFused gradients
   double* partials = nullptr;  // kNumNorms doubles per workgroup of the apply launch
@@ -74,6 +76,7 @@ struct rudra_ps {
   // statistics
   std::vector<uint64_t> hist;
   uint64_t n_pushes = 0, n_updates = 0, n_rejected = 0, sigma_sum = 0, sigma_max = 0;
+  uint64_t n_weight_copies = 0, n_ts_inquiries = 0, n_weight_views = 0;
   double last_avg = 0.0;
   float last_lr = 0.f;
   uint32_t last_apply_blocks = 0;
@@ -197,7 +200,8 @@ void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, cons
 UpdateArgs base_args(const rudra_ps* ps) {
   UpdateArgs a;
   std::memset(&a, 0, sizeof(a));
-  a.theta = ps->theta;
+  a.theta = ps->theta2[ps->cur];
+  a.theta_out = ps->theta2[ps->double_buffer ? (ps->cur ^ 1u) : ps->cur];
   a.vel = ps->vel;
   a.sum_out = ps->acc;
   a.partials = ps->partials;
@@ -290,6 +294,7 @@ int enqueue_update(rudra_ps* ps, float lr) {
     ps->timed_launches += 1;
   }
   ps->last_apply_blocks = s.grid;
+  if (ps->double_buffer) ps->cur ^= 1u;  // the pointer swap: the buffer just written now holds the current weights
   return RUDRA_OK;
 }
 
@@ -316,7 +321,8 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->launch_waves_per_cu && (c->launch_waves_per_cu < 2 || c->launch_waves_per_cu > 32)) return RUDRA_EINVAL;
   if ((c->launch_unroll ? c->launch_unroll : kDefaultUnroll) * (c->launch_vec ? c->launch_vec : kDefaultVec) > 8)
     return RUDRA_EINVAL;  // more 16-byte loads per lane than the register file holds without spilling
-  if (c->flags & ~(uint32_t)(RUDRA_FLAG_STATS_NORMS | RUDRA_FLAG_PUSH_ACCUMULATE | RUDRA_FLAG_CONTROL_ONLY | RUDRA_FLAG_TIME_KERNELS))
+  if (c->flags & ~(uint32_t)(RUDRA_FLAG_STATS_NORMS | RUDRA_FLAG_PUSH_ACCUMULATE | RUDRA_FLAG_CONTROL_ONLY | RUDRA_FLAG_TIME_KERNELS |
+                              RUDRA_FLAG_DOUBLE_BUFFER))
     return RUDRA_EINVAL;
   if (!(c->alpha0 == c->alpha0) || !(c->lr_scale == c->lr_scale) || !(c->momentum == c->momentum) ||
       !(c->weight_decay == c->weight_decay))
@@ -330,7 +336,8 @@ void release(rudra_ps* ps) {
     (void)hipStreamSynchronize(ps->stream);
     for (hipEvent_t e : ps->ev_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : ps->ev_stop) (void)hipEventDestroy(e);
-    if (ps->theta) (void)hipFree(ps->theta);
+    if (ps->theta2[0]) (void)hipFree(ps->theta2[0]);
+    if (ps->theta2[1]) (void)hipFree(ps->theta2[1]);
     if (ps->vel) (void)hipFree(ps->vel);
     if (ps->acc) (void)hipFree(ps->acc);
     if (ps->partials) (void)hipFree(ps->partials);
@@ -358,6 +365,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   ps->accumulate = (config->flags & RUDRA_FLAG_PUSH_ACCUMULATE) != 0;
   ps->want_norms = (config->flags & RUDRA_FLAG_STATS_NORMS) != 0 && !control_only;
   ps->time_kernels = (config->flags & RUDRA_FLAG_TIME_KERNELS) != 0 && !control_only;
+  ps->double_buffer = (config->flags & RUDRA_FLAG_DOUBLE_BUFFER) != 0 && !control_only;
   ps->stream = (hipStream_t)config->stream;
   ps->c = gradients_per_update(*config);
   if (config->launch_block) ps->block = config->launch_block;
@@ -392,10 +400,11 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   if (!control_only) {
     const size_t bytes = config->n_params * sizeof(float);
     hipError_t e = hipSetDevice(config->device);
-    if (e == hipSuccess) e = hipMalloc((void**)&ps->theta, bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&ps->theta2[0], bytes);
+    if (e == hipSuccess && ps->double_buffer) e = hipMalloc((void**)&ps->theta2[1], bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ps->vel, bytes);
     if (e == hipSuccess && ps->accumulate) e = hipMalloc((void**)&ps->acc, bytes);
-    if (e == hipSuccess) e = hipMemcpyAsync(ps->theta, init_weights, bytes, hipMemcpyDeviceToDevice, ps->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(ps->theta2[0], init_weights, bytes, hipMemcpyDeviceToDevice, ps->stream);
     if (e == hipSuccess) e = hipMemsetAsync(ps->vel, 0, bytes, ps->stream);
     if (e == hipSuccess && ps->want_norms) {
       ps->partials_blocks = shape_for(ps).grid;
@@ -507,9 +516,23 @@ int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out) {
     if (ps->control_only) return RUDRA_ESTATE;
     if (ps->failed) return RUDRA_EHIP;
     RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
-    RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->theta, ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+    RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->theta2[ps->cur], ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+    ps->n_weight_copies += 1;
+  } else {
+    ps->n_ts_inquiries += 1;
   }
   if (ts_out) *ts_out = ps->ts_cur;
+  return RUDRA_OK;
+}
+
+int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_out) {
+  if (!ps || !theta_out) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  *theta_out = ps->theta2[ps->cur];
+  if (ts_out) *ts_out = ps->ts_cur;
+  ps->n_weight_views += 1;
   return RUDRA_OK;
 }
 
@@ -541,6 +564,9 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
   out->c = ps->c;
   out->last_lr = ps->last_lr;
   out->last_hip_error = ps->last_hip_error;
+  out->n_weight_copies = ps->n_weight_copies;
+  out->n_ts_inquiries = ps->n_ts_inquiries;
+  out->n_weight_views = ps->n_weight_views;
   if (ps->failed) return RUDRA_EHIP;
   if (ps->time_kernels) {
     RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));

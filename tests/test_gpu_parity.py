@@ -296,3 +296,60 @@ def test_full_size_full_length_parity_on_sampled_elements(hipmod, name):
     full = hip.weights()
     assert bool(torch.isfinite(full).all())
     hip.close()
+
+
+# ---------------------------------------------------------------- double-buffered weights, zero-copy pull
+def _read_device(ptr, n):
+    """Copy n floats from a raw device address into a numpy array (synchronous hipMemcpy)."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    out = np.empty(n, np.float32)
+    assert hip.hipMemcpy(out.ctypes.data, ptr, n * 4, 2) == 0       # 2 = device to host
+    return out
+
+
+@pytest.mark.parametrize("name", ["C4", "C5", "C4-adagrad"])
+def test_double_buffer_gives_the_same_bits(hipmod, name):
+    from paper_1509_04210_amd import binding as B
+    base, P, n = SMALL[name]
+    w = base.scaled(n_params=P, n_pushes=n)
+    hip, ora = _run_both(hipmod, w, flags=B.FLAG_DOUBLE_BUFFER)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+def test_weights_view_stays_valid_while_the_next_update_runs(hipmod):
+    """Sec. 3.3 pointer swap, server side: the weights of timestamp i remain readable, unchanged, until update i+2."""
+    from paper_1509_04210_amd import binding as B
+    w = configs.C3(2).scaled(n_params=70_001, n_pushes=15 * 6)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w, flags=B.FLAG_DOUBLE_BUFFER), OracleServer(w)
+    views, refs, ts_l = [], [], [0] * w.n_learners
+    for i in range(len(learner)):
+        l, s = int(learner[i]), int(step[i])
+        _, _, applied = hip.push(l, s, ts_l[l])
+        ora.push(l, s, ts_l[l])
+        ts_l[l] = hip.pull_ts()
+        if applied:
+            ptr, ts = hip.ps.weights_view()
+            assert ts == ora.ps.ts
+            views.append(ptr)
+            refs.append(ora.ps.theta)
+            hip.ps.sync()
+            assert np.array_equal(_read_device(ptr, w.n_params), refs[-1])              # the current weights
+            if len(views) >= 2:                                                          # the previous ones: still intact
+                assert views[-2] != ptr
+                assert np.array_equal(_read_device(views[-2], w.n_params), refs[-2])
+            if len(views) >= 3:
+                assert views[-3] == ptr                                                  # two buffers, ping-pong
+    assert len(views) == 6
+    st = hip.ps.stats()
+    assert st.n_weight_views == 6 and st.n_weight_copies == 0 and st.n_ts_inquiries == len(learner)
+    hip.close()
+    single = hipmod.HipServer(w)                  # without the flag there is one buffer
+    p0, _ = single.ps.weights_view()
+    for i in range(15):
+        single.push(int(learner[i]), int(step[i]), 0)
+    assert single.ps.weights_view() == (p0, 1)
+    single.close()
