@@ -1,0 +1,91 @@
+// Host-only driver for sanitizer runs: exercises the library's control plane (RUDRA_FLAG_CONTROL_ONLY: no device
+// work) through the C ABI: rejections, ring eviction, histogram growth, clocks, statistics, many threads.
+#include <cstdio>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "../../include/rudra_ps.h"
+
+#define CHECK(cond)                                              \
+  do {                                                           \
+    if (!(cond)) {                                               \
+      std::printf("CHECK failed line %d: %s\n", __LINE__, #cond); \
+      return 1;                                                  \
+    }                                                            \
+  } while (0)
+
+int main() {
+  rudra_ps_config_t cfg;
+  std::memset(&cfg, 0, sizeof(cfg));
+  cfg.n_params = 1000;
+  cfg.n_learners = 7;
+  cfg.n_split = 2;  // c = 3
+  cfg.protocol = RUDRA_SOFTSYNC;
+  cfg.lr_mode = RUDRA_LR_AVG_STALENESS;
+  cfg.alpha0 = 0.01f;
+  cfg.lr_scale = 1.0f;
+  cfg.flags = RUDRA_FLAG_CONTROL_ONLY;
+  cfg.clock_ring = 5;
+  rudra_ps_t* ps = nullptr;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_OK);
+  rudra_push_result_t r;
+  uint64_t ts = 0;
+  for (int i = 0; i < 300; ++i) {
+    const uint64_t stamp = (i % 11 == 0) ? 0 : ts;  // occasionally very stale: the histogram has to grow
+    CHECK(rudra_ps_push_gradient(ps, nullptr, stamp, i % 7, &r) == RUDRA_OK);
+    CHECK(r.staleness == ts - stamp);
+    ts = r.ts_after;
+  }
+  CHECK(ts == 100);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, ts + 1, 0, &r) == RUDRA_EFUTURE_TS);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, ts, 7, &r) == RUDRA_EINVAL);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, ts, -2, nullptr) == RUDRA_EINVAL);
+  uint64_t clock[3];
+  uint32_t n = 0;
+  double avg = 0;
+  float lr = 0;
+  CHECK(rudra_ps_vector_clock(ps, 99, clock, 3, &n, &avg, &lr) == RUDRA_OK && n == 3);
+  CHECK(rudra_ps_vector_clock(ps, 95, clock, 3, &n, nullptr, nullptr) == RUDRA_OK);
+  CHECK(rudra_ps_vector_clock(ps, 94, clock, 3, &n, nullptr, nullptr) == RUDRA_ERANGE);   // left the ring of 5
+  CHECK(rudra_ps_vector_clock(ps, 100, clock, 3, &n, nullptr, nullptr) == RUDRA_ERANGE);  // not yet
+  CHECK(rudra_ps_vector_clock(ps, 99, clock, 2, &n, nullptr, nullptr) == RUDRA_ERANGE);   // buffer too small
+  rudra_ps_stats_t st;
+  CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK);
+  CHECK(st.n_pushes == 300 && st.n_updates == 100 && st.n_rejected == 3 && st.pending == 0 && st.c == 3);
+  std::vector<uint64_t> hist(st.hist_len);
+  uint64_t hn = 0;
+  CHECK(rudra_ps_staleness_hist(ps, hist.data(), 1, &hn) == RUDRA_ERANGE && hn == st.hist_len);
+  CHECK(rudra_ps_staleness_hist(ps, hist.data(), hist.size(), &hn) == RUDRA_OK);
+  uint64_t total = 0, weighted = 0;
+  for (size_t s = 0; s < hist.size(); ++s) { total += hist[s]; weighted += s * hist[s]; }
+  CHECK(total == 300 && weighted == st.sigma_sum && st.sigma_max + 1 == st.hist_len);
+  float dummy;
+  CHECK(rudra_ps_pull_weights(ps, &dummy, &ts) == RUDRA_ESTATE);
+  CHECK(rudra_ps_pull_weights(ps, nullptr, &ts) == RUDRA_OK && ts == 100);
+  const float* view = nullptr;
+  CHECK(rudra_ps_weights_view(ps, &view, nullptr) == RUDRA_ESTATE);
+  CHECK(rudra_ps_set_lr(ps, 0.001f) == RUDRA_OK && rudra_ps_sync(ps) == RUDRA_OK);
+  // many threads at once: the mutex serialises them
+  std::vector<std::thread> th;
+  for (int t = 0; t < 6; ++t)
+    th.emplace_back([ps, t] { for (int i = 0; i < 3000; ++i) rudra_ps_push_gradient(ps, nullptr, 0, t, nullptr); });
+  for (auto& x : th) x.join();
+  CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK);
+  CHECK(st.n_pushes == 300 + 18000 && st.n_updates == 100 + 6000);
+  CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+  // hardsync: duplicates and stale gradients
+  cfg.protocol = RUDRA_HARDSYNC;
+  cfg.lr_mode = RUDRA_LR_CONST;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_OK);
+  for (int l = 0; l < 6; ++l) CHECK(rudra_ps_push_gradient(ps, nullptr, 0, l, &r) == RUDRA_OK && !r.applied);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, 0, 3, &r) == RUDRA_EHARDSYNC_DUP);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, 0, 6, &r) == RUDRA_OK && r.applied && r.ts_after == 1);
+  CHECK(rudra_ps_push_gradient(ps, nullptr, 0, 0, &r) == RUDRA_EHARDSYNC_STALE);
+  CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+  cfg.n_split = 9;
+  cfg.protocol = RUDRA_SOFTSYNC;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL && ps == nullptr);
+  std::printf("host driver ok\n");
+  return 0;
+}
