@@ -62,10 +62,13 @@ enum rudra_flags {
   RUDRA_FLAG_CONTROL_ONLY = 4u,    /* timestamps, staleness, clocks and rates only: no device memory, no kernels;
                                       grad may be NULL; pulling weights is an error.  For host-side tests. */
   RUDRA_FLAG_TIME_KERNELS = 8u,    /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t */
-  RUDRA_FLAG_DOUBLE_BUFFER = 16u   /* keep two weight buffers: update i reads one and writes the other (no extra traffic),
+  RUDRA_FLAG_DOUBLE_BUFFER = 16u,  /* keep two weight buffers: update i reads one and writes the other (no extra traffic),
                                       so the weights of timestamp ts stay readable while update ts+1 runs: the
                                       computation-buffer / communication-buffer pair with a pointer swap of Sec. 3.3,
                                       on the server side.  See rudra_ps_weights_view.  Costs 4P bytes of HBM. */
+  RUDRA_FLAG_CHECK_POINTERS = 32u  /* ask the HIP runtime about every pushed pointer (device memory of this device, at
+                                      least 4P bytes to the end of its allocation) and reject it with EINVAL otherwise,
+                                      instead of letting a kernel fault on it; a few microseconds per push */
 };
 
 enum rudra_status {
@@ -146,7 +149,7 @@ typedef struct {
   uint64_t n_weight_views;  /* rudra_ps_weights_view calls */
 } rudra_ps_stats_t;
 
-/* Create a server.  init_weights: DEVICE pointer to P floats, copied (the caller keeps its buffer); in
+/* Create a server.  init_weights: DEVICE pointer to P floats (checked with the HIP runtime), copied (the caller keeps its buffer); in
  * CONTROL_ONLY mode it is ignored and may be NULL.  theta, v and any scratch are allocated with hipMalloc and
  * owned by the library until rudra_ps_destroy.  Timestamp starts at 0 (Sec. 3.1), v at 0.
  * Errors: EINVAL (bad config / null), ENOMEM, EHIP. */

@@ -16,6 +16,7 @@ HARDSYNC, SOFTSYNC = 0, 1
 LR_CONST, LR_STATIC_N, LR_AVG_STALENESS, LR_PER_GRADIENT = 0, 1, 2, 3
 OPT_SGD, OPT_ADAGRAD = 0, 1
 FLAG_STATS_NORMS, FLAG_PUSH_ACCUMULATE, FLAG_CONTROL_ONLY, FLAG_TIME_KERNELS, FLAG_DOUBLE_BUFFER = 1, 2, 4, 8, 16
+FLAG_CHECK_POINTERS = 32
 OK, EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, ENOMEM, EHIP, ERANGE, ESTATE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 

@@ -42,7 +42,7 @@ struct rudra_ps {
   std::mutex mu;
   hipStream_t stream = nullptr;
   uint32_t c = 0;
-  bool control_only = false, accumulate = false, want_norms = false, time_kernels = false;
+  bool control_only = false, accumulate = false, want_norms = false, time_kernels = false, check_pointers = false;
   bool failed = false;
   int last_hip_error = 0;
 
@@ -298,6 +298,25 @@ int enqueue_update(rudra_ps* ps, float lr) {
   return RUDRA_OK;
 }
 
+// true if [p, p + bytes) is device memory of `device` according to the HIP runtime
+bool is_device_range(const void* p, size_t bytes, int device) {
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+    (void)hipGetLastError();  // the query of a non-HIP pointer leaves an error behind: clear it
+    return false;
+  }
+  if (attr.type != hipMemoryTypeDevice || attr.device != device) return false;
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  const char* lo = static_cast<const char*>(base);
+  const char* q = static_cast<const char*>(p);
+  return q >= lo && bytes <= size && (size_t)(q - lo) <= size - bytes;
+}
+
 void count_staleness(rudra_ps* ps, uint64_t sigma) {
   if (sigma >= ps->hist.size()) ps->hist.resize(sigma + 1, 0);
   ps->hist[sigma] += 1;
@@ -322,7 +341,7 @@ int validate_config(const rudra_ps_config_t* c) {
   if ((c->launch_unroll ? c->launch_unroll : kDefaultUnroll) * (c->launch_vec ? c->launch_vec : kDefaultVec) > 8)
     return RUDRA_EINVAL;  // more 16-byte loads per lane than the register file holds without spilling
   if (c->flags & ~(uint32_t)(RUDRA_FLAG_STATS_NORMS | RUDRA_FLAG_PUSH_ACCUMULATE | RUDRA_FLAG_CONTROL_ONLY | RUDRA_FLAG_TIME_KERNELS |
-                              RUDRA_FLAG_DOUBLE_BUFFER))
+                              RUDRA_FLAG_DOUBLE_BUFFER | RUDRA_FLAG_CHECK_POINTERS))
     return RUDRA_EINVAL;
   if (!(c->alpha0 == c->alpha0) || !(c->lr_scale == c->lr_scale) || !(c->momentum == c->momentum) ||
       !(c->weight_decay == c->weight_decay))
@@ -366,6 +385,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   ps->want_norms = (config->flags & RUDRA_FLAG_STATS_NORMS) != 0 && !control_only;
   ps->time_kernels = (config->flags & RUDRA_FLAG_TIME_KERNELS) != 0 && !control_only;
   ps->double_buffer = (config->flags & RUDRA_FLAG_DOUBLE_BUFFER) != 0 && !control_only;
+  ps->check_pointers = (config->flags & RUDRA_FLAG_CHECK_POINTERS) != 0 && !control_only;
   ps->stream = (hipStream_t)config->stream;
   ps->c = gradients_per_update(*config);
   if (config->launch_block) ps->block = config->launch_block;
@@ -400,6 +420,10 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   if (!control_only) {
     const size_t bytes = config->n_params * sizeof(float);
     hipError_t e = hipSetDevice(config->device);
+    if (e == hipSuccess && !is_device_range(init_weights, bytes, config->device)) {
+      delete ps;
+      return RUDRA_EINVAL;  // not P floats of this device's memory
+    }
     if (e == hipSuccess) e = hipMalloc((void**)&ps->theta2[0], bytes);
     if (e == hipSuccess && ps->double_buffer) e = hipMalloc((void**)&ps->theta2[1], bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ps->vel, bytes);
@@ -441,6 +465,10 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
   // ---- validation: a rejected message changes nothing but the rejection counter ----
   if (!ps->control_only && (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u))) { ps->n_rejected++; return RUDRA_EINVAL; }
   if (learner < -1 || learner >= (int32_t)cfg.n_learners) { ps->n_rejected++; return RUDRA_EINVAL; }
+  if (ps->check_pointers) {
+    if (hipSetDevice(cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
+    if (!is_device_range(grad, cfg.n_params * sizeof(float), cfg.device)) { ps->n_rejected++; return RUDRA_EINVAL; }
+  }
   if (ts > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
   if (cfg.protocol == RUDRA_HARDSYNC) {
     if (ts != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }

@@ -353,3 +353,44 @@ def test_weights_view_stays_valid_while_the_next_update_runs(hipmod):
         single.push(int(learner[i]), int(step[i]), 0)
     assert single.ps.weights_view() == (p0, 1)
     single.close()
+
+
+def test_pointer_check_rejects_what_a_kernel_would_fault_on(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = _with(configs.C1.scaled(n_params=10_000, n_pushes=8), n_learners=2, n_split=1)
+    hip = hipmod.HipServer(w, flags=B.FLAG_CHECK_POINTERS)
+    before = hip.weights().cpu().numpy()
+    host = np.zeros(10_016, np.float32)
+    host_ptr = (host.ctypes.data + 15) & ~15
+    import ctypes
+    rt = ctypes.CDLL("libamdhip64.so")          # raw allocations: torch carves its tensors out of larger blocks
+    rt.hipMalloc.argtypes, rt.hipMemset.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t], [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t]
+
+    def raw(nbytes):
+        p = ctypes.c_void_p()
+        assert rt.hipMalloc(ctypes.byref(p), nbytes) == 0 and rt.hipMemset(p, 0, nbytes) == 0
+        return p.value
+
+    small, late_base = raw(20_000), raw(40_016)
+
+    class _P:                                    # same accessors as a tensor, for the lines below
+        def __init__(self, p): self.p = p
+        def data_ptr(self): return self.p
+    small, late = _P(small), _P(late_base)
+    good = torch.ones(10_000, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    assert hip.ps.push_gradient(host_ptr, 0, 0)[0] == B.EINVAL                  # host memory
+    assert hip.ps.push_gradient(small.data_ptr(), 0, 0)[0] == B.EINVAL          # too short
+    assert hip.ps.push_gradient(late.data_ptr() + 32, 0, 0)[0] == B.EINVAL      # runs 16 bytes past its allocation
+    assert hip.ps.push_gradient(0x10000, 0, 0)[0] == B.EINVAL                   # not a HIP pointer at all
+    assert hip.ps.push_gradient(good.data_ptr(), 0, 0)[0] == B.OK
+    rc, r = hip.ps.push_gradient(late.data_ptr() + 16, 0, 1)                    # fits exactly
+    assert rc == B.OK and r.applied == 1
+    after = hip.weights().cpu().numpy()
+    assert np.array_equal(after, before - np.float32(w.alpha0) * (np.float32(1.0) * np.float32(0.5)))   # gradients: ones, zeros
+    st = hip.ps.stats()
+    assert st.n_rejected == 4 and st.last_hip_error == 0
+    with pytest.raises(B.RudraError) as e:                                       # create() always checks init_weights
+        B.ParameterServer(10_000, 2, host_ptr)
+    assert e.value.status == B.EINVAL
+    hip.close()
