@@ -396,11 +396,14 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   if (config->launch_waves_per_cu) {
     ps->waves_per_cu = config->launch_waves_per_cu;
   } else {
-    // about kInFlightKiBPerCu KiB of loads in flight per CU: each resident wave has theta, v and up to `unroll`
-    // gradient loads (1 KiB each) outstanding
+    // about kInFlightKiBPerCu KiB of loads in flight per CU: each resident wave has theta, the second state vector
+    // and up to `unroll` gradient loads (1 KiB each) outstanding.  Waves that issue everything in one round
+    // (c <= unroll) spend a larger share of their life outside the load phase, so they get at least 12 slots
+    // (measured at 72M: c = 4 runs at 6.7-6.8 TB/s with 12 waves, 6.2-6.3 with 8).
     const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (kernel_optimizer(*config) != rudra::kOptSgd ? 1u : 0u);
     const uint32_t waves_per_wg = ps->block / 64;
     uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
+    if (ps->c <= ps->unroll) w = std::max(w, 12u);
     w = std::max(w, std::max(4u, waves_per_wg));
     ps->waves_per_cu = std::min(w, 32u);
   }
