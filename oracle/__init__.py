@@ -49,7 +49,8 @@ class _Config(C.Structure):
     _fields_ = [("n_params", C.c_uint64), ("n_learners", C.c_uint32), ("n_split", C.c_uint32),
                 ("c_override", C.c_uint32), ("protocol", C.c_int32), ("lr_mode", C.c_int32),
                 ("alpha0", C.c_float), ("lr_scale", C.c_float), ("momentum", C.c_float),
-                ("weight_decay", C.c_float), ("optimizer", C.c_int32), ("adagrad_eps", C.c_float)]
+                ("weight_decay", C.c_float), ("optimizer", C.c_int32), ("adagrad_eps", C.c_float),
+                ("max_aggregate", C.c_uint32)]
 
 
 class PushResult(C.Structure):
@@ -74,6 +75,10 @@ def _load():
             f("destroy").restype = None
             f("push").argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.POINTER(PushResult)]
             f("push").restype = C.c_int
+            f("push_aggregate").argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(PushResult)]
+            f("push_aggregate").restype = C.c_int
+            f("leaf_mean").argtypes = [C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p]
+            f("leaf_mean").restype = None
             f("pull").argtypes = [C.c_void_p, C.c_void_p]
             f("pull").restype = C.c_uint64
             f("gradients_per_update").argtypes = [C.POINTER(_Config)]
@@ -85,18 +90,27 @@ def _load():
             for n in ("n_updates", "n_pushes", "n_rejected", "sigma_sum", "sigma_max", "hist_len"):
                 f(n).argtypes = [C.c_void_p]
                 f(n).restype = C.c_uint64
-            for n in ("pending", "c"):
+            for n in ("pending", "c", "clock_cap"):
                 f(n).argtypes = [C.c_void_p]
                 f(n).restype = C.c_uint32
-            for n in ("theta", "velocity", "hist", "clocks", "avg_staleness", "lr_log"):
+            for n in ("theta", "velocity", "hist", "clocks", "counts", "avg_staleness", "lr_log"):
                 f(n).argtypes = [C.c_void_p]
                 f(n).restype = C.c_void_p
     return _lib
 
 
 def gradients_per_update(n_learners, n_split=1, protocol=SOFTSYNC, c_override=0) -> int:
-    cfg = _Config(1, n_learners, n_split, c_override, protocol, LR_CONST, 0, 1, 0, 0, OPT_SGD, 0)
+    cfg = _Config(1, n_learners, n_split, c_override, protocol, LR_CONST, 0, 1, 0, 0, OPT_SGD, 0, 0)
     return int(_load().oracle32_gradients_per_update(C.byref(cfg)))
+
+
+def leaf_mean(grads, precision=32):
+    """Average relayed by a tree node: (g_1 + ... + g_k) * (1/k) in arrival order, as binary32."""
+    gs = [np.ascontiguousarray(g, dtype=np.float32) for g in grads]
+    ptrs = (C.c_void_p * len(gs))(*[g.ctypes.data for g in gs])
+    out = np.empty(gs[0].size, np.float32)
+    getattr(_load(), ("oracle32_" if precision == 32 else "oracle64_") + "leaf_mean")(ptrs, len(gs), gs[0].size, out.ctypes.data)
+    return out
 
 
 class OracleError(Exception):
@@ -111,7 +125,8 @@ class OraclePS:
 
     def __init__(self, init_weights, n_learners, n_split=1, protocol=SOFTSYNC,
                  lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0,
-                 weight_decay=0.0, c_override=0, precision=32, optimizer=OPT_SGD, adagrad_eps=1e-8):
+                 weight_decay=0.0, c_override=0, precision=32, optimizer=OPT_SGD, adagrad_eps=1e-8,
+                 max_aggregate=0):
         lib = _load()
         assert precision in (32, 64)
         self._p = "oracle32_" if precision == 32 else "oracle64_"
@@ -119,7 +134,7 @@ class OraclePS:
         w = np.ascontiguousarray(init_weights, dtype=np.float32)
         self.n_params = int(w.size)
         self.cfg = _Config(self.n_params, n_learners, n_split, c_override, protocol, lr_mode,
-                           alpha0, lr_scale, momentum, weight_decay, optimizer, adagrad_eps)
+                           alpha0, lr_scale, momentum, weight_decay, optimizer, adagrad_eps, max_aggregate)
         h = C.c_void_p()
         rc = getattr(lib, self._p + "create")(C.byref(self.cfg), w.ctypes.data, C.byref(h))
         if rc != OK:
@@ -143,6 +158,15 @@ class OraclePS:
         assert g.size == self.n_params
         res = PushResult()
         rc = self._f("push")(self._h, g.ctypes.data, int(ts), int(learner), C.byref(res))
+        return rc, res
+
+    def push_aggregate(self, avg, ts_list):
+        """A relayed average standing for len(ts_list) learner gradients.  Returns (rc, PushResult)."""
+        g = np.ascontiguousarray(avg, dtype=np.float32)
+        assert g.size == self.n_params
+        ts = np.ascontiguousarray(ts_list, dtype=np.uint64)
+        res = PushResult()
+        rc = self._f("push_aggregate")(self._h, g.ctypes.data, ts.ctypes.data, int(ts.size), C.byref(res))
         return rc, res
 
     def pull(self, want_weights=True):
@@ -211,8 +235,14 @@ class OraclePS:
 
     @property
     def clocks(self):
-        """(n_updates, c) timestamps of the gradients that triggered each update."""
-        return self._array("clocks", self.n_updates * self.c, np.uint64).reshape(self.n_updates, self.c)
+        """Timestamps of the gradients that triggered each update: an (n_updates, c) array, or, when relayed
+        averages made some updates collect more than c gradients, a list of arrays."""
+        cap = int(self._f("clock_cap")(self._h))
+        rows = self._array("clocks", self.n_updates * cap, np.uint64).reshape(self.n_updates, cap)
+        counts = self._array("counts", self.n_updates, np.uint32)
+        if cap == self.c or (counts == self.c).all():
+            return rows[:, :self.c]
+        return [rows[u, :counts[u]] for u in range(self.n_updates)]
 
     @property
     def avg_staleness(self):

@@ -50,13 +50,16 @@
  *   - momentum: v <- m*v - alpha*gbar ; theta <- theta + v   (rate inside the
  *     velocity, the convention of the networks the paper says it follows);
  *   - weight penalty: L2, gbar <- gbar + wd*theta before rate and momentum;
+ *   - tree of servers (Sec. 3.3): a node relays (g_1+...+g_k)*(1/k) together with its constituents' timestamps;
+ *     the root adds m*avg for a message standing for m gradients, fires at "at least c" and divides by the
+ *     number collected (the paper says neither which timestamp a relayed average carries nor when a node relays);
  *   - per-gradient modulation (Sec. 5.1 footnote, not explored by the paper):
  *     each arriving gradient is scaled by 1/max(1, sigma_l) before it is added;
  *     the update then uses alpha0*lr_scale.
  *   - AdaGrad: the cited diagonal rule, h <- h + gbar^2, theta <- theta - alpha*gbar/(sqrt(h)+eps),
  *     the weight penalty added to gbar first, alpha the staleness-modulated rate, no momentum.
- *   PARITY UNPINNED BY THE PAPER: the momentum, weight-penalty and AdaGrad formulas and the
- *   per-gradient modulation (no formula is printed); they are pinned only against
+ *   PARITY UNPINNED BY THE PAPER: the momentum, weight-penalty and AdaGrad formulas, the tree's
+ *   bookkeeping and the per-gradient modulation (no formula is printed); they are pinned only against
  *   library SGD / Adagrad routines and closed forms.
  */
 #include <math.h>
@@ -98,6 +101,7 @@ typedef struct {
   float alpha0, lr_scale, momentum, weight_decay;
   int32_t optimizer;   /* OPT_SGD (with optional momentum) or OPT_ADAGRAD */
   float adagrad_eps;   /* added to sqrt(h) */
+  uint32_t max_aggregate; /* largest number of learner gradients one relayed message may stand for (0 or 1: none) */
 } oracle_config;
 
 typedef struct {
@@ -115,11 +119,13 @@ typedef struct {
   uint64_t ts_cur;
   uint32_t count;
   uint64_t sigma_sum_open; /* sum of sigma over the open clock */
-  uint64_t *open_clock;    /* c entries */
+  uint32_t clock_cap;      /* c + max_aggregate - 1: an update can overshoot c by one message */
+  uint64_t *open_clock;    /* clock_cap entries */
   uint8_t *seen;           /* hardsync: learner already contributed this step */
   /* log of every closed vector clock */
   uint64_t n_updates, cap_updates;
-  uint64_t *clocks;        /* n_updates * c timestamps */
+  uint64_t *clocks;        /* n_updates * clock_cap timestamps (the first counts[u] of each row are used) */
+  uint32_t *counts;        /* gradients in each update */
   double *avg_staleness;   /* per update */
   float *lr_used;          /* per update */
   /* staleness histogram and counters */
@@ -140,7 +146,7 @@ uint32_t FN(gradients_per_update)(const oracle_config *cfg) { return gradients_p
 void FN(destroy)(oracle_t *o) {
   if (!o) return;
   free(o->theta); free(o->vel); free(o->acc); free(o->open_clock); free(o->seen);
-  free(o->clocks); free(o->avg_staleness); free(o->lr_used); free(o->hist);
+  free(o->clocks); free(o->counts); free(o->avg_staleness); free(o->lr_used); free(o->hist);
   free(o);
 }
 
@@ -164,7 +170,8 @@ int FN(create)(const oracle_config *cfg, const float *init_weights, oracle_t **o
   o->theta = (real *)malloc(P * sizeof(real));
   o->vel = (real *)calloc(P, sizeof(real));
   o->acc = (real *)calloc(P, sizeof(real));
-  o->open_clock = (uint64_t *)calloc(o->c, sizeof(uint64_t));
+  o->clock_cap = o->c + (cfg->max_aggregate > 1 ? cfg->max_aggregate - 1 : 0);
+  o->open_clock = (uint64_t *)calloc(o->clock_cap, sizeof(uint64_t));
   o->seen = (uint8_t *)calloc(cfg->n_learners, 1);
   o->hist_len = 16;
   o->hist = (uint64_t *)calloc(o->hist_len, sizeof(uint64_t));
@@ -180,16 +187,19 @@ int FN(create)(const oracle_config *cfg, const float *init_weights, oracle_t **o
 static int log_update(oracle_t *o, double avg_sigma, float lr) {
   if (o->n_updates == o->cap_updates) {
     uint64_t cap = o->cap_updates ? 2 * o->cap_updates : 64;
-    uint64_t *cl = (uint64_t *)realloc(o->clocks, cap * o->c * sizeof(uint64_t));
+    uint64_t *cl = (uint64_t *)realloc(o->clocks, cap * o->clock_cap * sizeof(uint64_t));
     if (cl) o->clocks = cl;
+    uint32_t *cn = (uint32_t *)realloc(o->counts, cap * sizeof(uint32_t));
+    if (cn) o->counts = cn;
     double *av = (double *)realloc(o->avg_staleness, cap * sizeof(double));
     if (av) o->avg_staleness = av;
     float *lu = (float *)realloc(o->lr_used, cap * sizeof(float));
     if (lu) o->lr_used = lu;
-    if (!cl || !av || !lu) return OR_ENOMEM;
+    if (!cl || !cn || !av || !lu) return OR_ENOMEM;
     o->cap_updates = cap;
   }
-  memcpy(o->clocks + o->n_updates * o->c, o->open_clock, o->c * sizeof(uint64_t));
+  memcpy(o->clocks + o->n_updates * o->clock_cap, o->open_clock, o->clock_cap * sizeof(uint64_t));
+  o->counts[o->n_updates] = o->count;
   o->avg_staleness[o->n_updates] = avg_sigma;
   o->lr_used[o->n_updates] = lr;
   o->n_updates += 1;
@@ -214,7 +224,8 @@ static int count_staleness(oracle_t *o, uint64_t sigma) {
  * acc holds the sum of the c gradients of this update. */
 static void apply_update(oracle_t *o, real lr) {
   const uint64_t P = o->cfg.n_params;
-  const real inv_c = (real)1 / (real)o->c;
+  const real inv_c = (real)1 / (real)o->count;   /* the mean is over the gradients actually collected (= c unless a
+                                                     relayed average made the count overshoot) */
   const real m = (real)o->cfg.momentum;
   const real wd = (real)o->cfg.weight_decay;
   double gbar_sq = 0.0;
@@ -248,6 +259,45 @@ static void apply_update(oracle_t *o, real lr) {
   o->last_gbar_sq = gbar_sq;
 }
 
+/* applyUpdate when enough gradients have been collected: rate from this update's clock, update, clock closed. */
+static int maybe_update(oracle_t *o, int *applied, float *lr_used) {
+  *applied = 0;
+  *lr_used = 0.0f;
+  if (o->count < o->c) return OR_OK;               /* "at least c gradients" (Sec. 3.1) */
+  /* <sigma> = (i-1) - mean(i_1..i_count) with i-1 = ts_cur, i.e. mean of (ts_cur - i_k), Eq. 2 */
+  const double avg_sigma = (double)o->sigma_sum_open / (double)o->count;
+  double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;
+  if (o->cfg.lr_mode == LR_STATIC_N) lr = lr / (double)o->cfg.n_split;          /* alpha0/n */
+  else if (o->cfg.lr_mode == LR_AVG_STALENESS) lr = lr / (avg_sigma > 1.0 ? avg_sigma : 1.0);
+  *lr_used = (float)lr;   /* the rate is a binary32 number in both builds' logs */
+  real lr_work = (sizeof(real) == sizeof(float)) ? (real)*lr_used : (real)lr;
+  apply_update(o, lr_work);
+  int rc = log_update(o, avg_sigma, *lr_used);
+  if (rc != OR_OK) return rc;
+  o->ts_cur += 1;                                  /* each weight update increments the timestamp */
+  o->count = 0;
+  o->sigma_sum_open = 0;
+  memset(o->seen, 0, o->cfg.n_learners);
+  *applied = 1;
+  return OR_OK;
+}
+
+/* sigma = j - i for a gradient stamped i arriving when the weights are stamped j (Sec. 3.1) */
+static uint64_t staleness_of(const oracle_t *o, uint64_t ts) { return o->ts_cur - ts; }
+
+static int note_gradient(oracle_t *o, uint64_t ts) {   /* clock, staleness statistics, count */
+  const uint64_t sigma = staleness_of(o, ts);
+  int rc = count_staleness(o, sigma);
+  if (rc != OR_OK) return rc;
+  o->open_clock[o->count] = ts;
+  o->count += 1;
+  o->sigma_sum_open += sigma;
+  o->sigma_sum_all += sigma;
+  if (sigma > o->sigma_max) o->sigma_max = sigma;
+  o->n_pushes += 1;
+  return OR_OK;
+}
+
 /* pushGradient as the server sees it: one gradient (P binary32 values) stamped ts
  * from learner `learner` (-1 = anonymous).  A rejected message changes nothing. */
 int FN(push)(oracle_t *o, const float *grad, uint64_t ts, int32_t learner, oracle_push_result *res) {
@@ -258,9 +308,7 @@ int FN(push)(oracle_t *o, const float *grad, uint64_t ts, int32_t learner, oracl
     if (ts != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; } /* staleness is always zero */
     if (learner >= 0 && o->seen[learner]) { o->n_rejected++; return OR_EHARDSYNC_DUP; } /* exactly one */
   }
-  const uint64_t sigma = o->ts_cur - ts;                               /* sigma = j - i */
-  int rc = count_staleness(o, sigma);
-  if (rc != OR_OK) return rc;
+  const uint64_t sigma = staleness_of(o, ts);
 
   /* sumGradients: receive and accumulate, in arrival order */
   const uint64_t P = o->cfg.n_params;
@@ -276,35 +324,66 @@ int FN(push)(oracle_t *o, const float *grad, uint64_t ts, int32_t learner, oracl
     for (uint64_t k = 0; k < P; ++k)
       o->acc[k] = (o->count == 0) ? (real)grad[k] : o->acc[k] + (real)grad[k];
   }
-  o->open_clock[o->count] = ts;
-  o->count += 1;
-  o->sigma_sum_open += sigma;
-  o->sigma_sum_all += sigma;
-  if (sigma > o->sigma_max) o->sigma_max = sigma;
-  o->n_pushes += 1;
+  int rc = note_gradient(o, ts);
+  if (rc != OR_OK) return rc;
   if (learner >= 0 && o->cfg.protocol == PROTO_HARDSYNC) o->seen[learner] = 1;
 
-  int applied = 0;
-  float lr_used = 0.0f;
-  if (o->count == o->c) {
-    /* <sigma> = (i-1) - mean(i_1..i_c) with i-1 = ts_cur, i.e. mean of (ts_cur - i_k) */
-    const double avg_sigma = (double)o->sigma_sum_open / (double)o->c;
-    double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;
-    if (o->cfg.lr_mode == LR_STATIC_N) lr = lr / (double)o->cfg.n_split;          /* alpha0/n */
-    else if (o->cfg.lr_mode == LR_AVG_STALENESS) lr = lr / (avg_sigma > 1.0 ? avg_sigma : 1.0);
-    lr_used = (float)lr;   /* the rate is a binary32 number in both builds' logs */
-    real lr_work = (sizeof(real) == sizeof(float)) ? (real)lr_used : (real)lr;
-    apply_update(o, lr_work);
-    rc = log_update(o, avg_sigma, lr_used);
-    if (rc != OR_OK) return rc;
-    o->ts_cur += 1;                                /* each weight update increments the timestamp */
-    o->count = 0;
-    o->sigma_sum_open = 0;
-    memset(o->seen, 0, o->cfg.n_learners);
-    applied = 1;
-  }
+  int applied;
+  float lr_used;
+  rc = maybe_update(o, &applied, &lr_used);
+  if (rc != OR_OK) return rc;
   if (res) {
     res->staleness = sigma;
+    res->ts_after = o->ts_cur;
+    res->pending = o->count;
+    res->applied = applied;
+    res->lr_used = lr_used;
+  }
+  return OR_OK;
+}
+
+/* A node of the parameter-server tree (Sec. 3.3): it averages the gradients sent by its learners and relays the
+ * average to its parent.  out = (g_1 + g_2 + ... + g_k) * (1/k), added in arrival order in the working precision,
+ * stored as binary32 (a relayed message is a model-sized binary32 vector like any other). */
+void FN(leaf_mean)(const float *const *grads, uint32_t k, uint64_t n, float *out) {
+  const real inv_k = (real)1 / (real)k;
+  for (uint64_t i = 0; i < n; ++i) {
+    real s = (real)grads[0][i];
+    for (uint32_t l = 1; l < k; ++l) s = s + (real)grads[l][i];
+    out[i] = (float)(s * inv_k);
+  }
+}
+
+/* The root receiving a relayed average that stands for m learner gradients with timestamps ts[0..m-1] (reading:
+ * the message carries its constituents' timestamps, so staleness, vector clock and <sigma> stay exact, Eq. 2).
+ * It counts as m gradients: the sum takes m*avg, the update fires once at least c gradients are in and averages
+ * over the number actually collected.  res->staleness reports the largest constituent staleness. */
+int FN(push_aggregate)(oracle_t *o, const float *avg, const uint64_t *ts, uint32_t m, oracle_push_result *res) {
+  if (!o || !avg || !ts || m == 0) return OR_EINVAL;
+  const uint32_t max_m = o->cfg.max_aggregate > 1 ? o->cfg.max_aggregate : 1;
+  if (m > max_m || o->cfg.lr_mode == LR_PER_GRADIENT) { o->n_rejected++; return OR_EINVAL; }
+  for (uint32_t j = 0; j < m; ++j) {
+    if (ts[j] > o->ts_cur) { o->n_rejected++; return OR_EFUTURE_TS; }
+    if (o->cfg.protocol == PROTO_HARDSYNC && ts[j] != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; }
+  }
+  const uint64_t P = o->cfg.n_params;
+  const real w = (real)m;
+  for (uint64_t k = 0; k < P; ++k) {
+    real scaled = w * (real)avg[k];
+    o->acc[k] = (o->count == 0) ? scaled : o->acc[k] + scaled;
+  }
+  uint64_t worst = 0;
+  for (uint32_t j = 0; j < m; ++j) {
+    if (staleness_of(o, ts[j]) > worst) worst = staleness_of(o, ts[j]);
+    int rc = note_gradient(o, ts[j]);
+    if (rc != OR_OK) return rc;
+  }
+  int applied;
+  float lr_used;
+  int rc = maybe_update(o, &applied, &lr_used);
+  if (rc != OR_OK) return rc;
+  if (res) {
+    res->staleness = worst;
     res->ts_after = o->ts_cur;
     res->pending = o->count;
     res->applied = applied;
@@ -333,6 +412,8 @@ uint64_t FN(sigma_max)(const oracle_t *o) { return o->sigma_max; }
 uint64_t FN(hist_len)(const oracle_t *o) { return o->hist_len; }
 const uint64_t *FN(hist)(const oracle_t *o) { return o->hist; }
 const uint64_t *FN(clocks)(const oracle_t *o) { return o->clocks; }
+const uint32_t *FN(counts)(const oracle_t *o) { return o->counts; }
+uint32_t FN(clock_cap)(const oracle_t *o) { return o->clock_cap; }
 const double *FN(avg_staleness)(const oracle_t *o) { return o->avg_staleness; }
 const float *FN(lr_log)(const oracle_t *o) { return o->lr_used; }
 int FN(set_alpha0)(oracle_t *o, float alpha0) { if (!o) return OR_EINVAL; o->cfg.alpha0 = alpha0; return OR_OK; }

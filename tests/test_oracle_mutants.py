@@ -11,14 +11,14 @@ import oracle
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = open(os.path.join(ROOT, "oracle", "rudra_oracle.c")).read()
-PINS = ["tests/test_oracle_protocol.py", "tests/test_oracle_update.py"]
+PINS = ["tests/test_oracle_protocol.py", "tests/test_oracle_update.py", "tests/test_oracle_tree.py"]
 
 MUTANTS = {
     "mean_not_divided_by_c": ("real gbar = o->acc[k] * inv_c;", "real gbar = o->acc[k];"),
     "update_sign": ("o->theta[k] = o->theta[k] - step;", "o->theta[k] = o->theta[k] + step;"),
     "momentum_sign": ("o->vel[k] = keep - step;", "o->vel[k] = keep + step;"),
     "weight_penalty_dropped": ("gbar = gbar + penalty;", "gbar = gbar;"),
-    "staleness_off_by_one": ("const uint64_t sigma = o->ts_cur - ts;", "const uint64_t sigma = o->ts_cur + 1 - ts;"),
+    "staleness_off_by_one": ("{ return o->ts_cur - ts; }", "{ return o->ts_cur + 1 - ts; }"),
     "rate_divisor_not_clamped": ("lr = lr / (avg_sigma > 1.0 ? avg_sigma : 1.0);", "lr = lr / (avg_sigma > 0.0 ? avg_sigma : 1.0);"),
     "c_rounded_up": ("return cfg->n_learners / cfg->n_split;", "return (cfg->n_learners + cfg->n_split - 1) / cfg->n_split;"),
     "rate_outside_velocity": ("o->vel[k] = keep - step;\n      o->theta[k] = o->theta[k] + o->vel[k];",
@@ -30,7 +30,11 @@ MUTANTS = {
     "per_gradient_weight_dropped": ("(real)(float)(1.0 / div) : (real)(1.0 / div)", "(real)1 : (real)1"),
     "static_rate_divides_by_c": ("lr = lr / (double)o->cfg.n_split;", "lr = lr / (double)o->c;"),
     "stale_hardsync_accepted": ("if (ts != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; }", ""),
-    "average_staleness_uses_sum": ("(double)o->sigma_sum_open / (double)o->c;", "(double)o->sigma_sum_open;"),
+    "average_staleness_uses_sum": ("(double)o->sigma_sum_open / (double)o->count;", "(double)o->sigma_sum_open;"),
+    "relayed_average_counts_once": ("  const real w = (real)m;", "  const real w = (real)1;"),
+    "mean_over_c_not_over_collected": ("const real inv_c = (real)1 / (real)o->count;", "const real inv_c = (real)1 / (real)o->c;"),
+    "leaf_relays_the_sum": ("out[i] = (float)(s * inv_k);", "out[i] = (float)s;"),
+    "update_waits_for_exactly_c": ("if (o->count < o->c) return OR_OK;", "if (o->count != o->c) return OR_OK;"),
     "adagrad_accumulator_not_summed": ("o->vel[k] = o->vel[k] + sq;", "o->vel[k] = sq;"),
     "adagrad_eps_inside_the_root": ("real denom = root + (real)o->cfg.adagrad_eps;", "real denom = (real)sqrt((double)o->vel[k] + (double)o->cfg.adagrad_eps);"),
     "adagrad_penalty_after_accumulator": ("      real sq = gbar * gbar;", "      real sq = (gbar - wd * o->theta[k]) * (gbar - wd * o->theta[k]);"),
