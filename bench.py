@@ -90,6 +90,49 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, **launch):
     return out
 
 
+def run_gpu_tree(w, fan_in, steps, warmup, ring=64):
+    """The same replay through a two-level server tree (Sec. 3.3): every `fan_in` gradients of a node are averaged on
+    the device (rudra_ps_leaf_mean) and the average is relayed to the root (rudra_ps_push_aggregate)."""
+    import torch
+    from paper_1509_04210_amd import binding as B
+    from paper_1509_04210_amd.learners import HipServer
+
+    n_msgs = w.c // fan_in                                   # relayed messages per update (c divisible by fan_in here)
+    hip = HipServer(w, pregenerated=ring, avg_ring=n_msgs + 4, max_aggregate=fan_in)
+    ps, bufs, avgs = hip.ps, [b.data_ptr() for b in hip.ring], [b.data_ptr() for b in hip.avg_ring]
+    P, sh = w.n_params, hip.sh
+    state = dict(g=0, a=0, ts=0)
+
+    def run_updates(n):
+        for _ in range(n * n_msgs):
+            ptrs = [bufs[(state["g"] + j) % len(bufs)] for j in range(fan_in)]
+            state["g"] += fan_in
+            avg = avgs[state["a"] % len(avgs)]
+            state["a"] += 1
+            B.leaf_mean(ptrs, P, avg, 0, sh)
+            rc, res = ps.push_aggregate(avg, [state["ts"]] * fan_in)
+            if rc != 0:
+                raise RuntimeError(f"relayed message rejected: {rc}")
+            state["ts"] = res.ts_after                       # learners re-pull after every push (zero-latency tree)
+
+    run_updates(warmup)
+    ps.sync()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(hip.stream)
+    t0 = time.perf_counter()
+    run_updates(steps)
+    e1.record(hip.stream)
+    ps.sync()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    assert ps.stats().n_updates == warmup + steps
+    hip.close()
+    torch.cuda.empty_cache()
+    return dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * w.c)
+
+
 def run_cpu_oracle(w, n_updates=30, n_distinct=3):
     """The CPU oracle as it stands, single thread, on the full-size vector: `n_updates` applyUpdates of the same
     workload.  Gradient materialisation is excluded from the timing (as on the GPU)."""
@@ -206,6 +249,23 @@ def main():
                 "avg_launch_ms": o_ms, "achieved_GBps": bo / (o_ms * 1e-3) / 1e9,
                 "frac": bo / (o_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "bytes_per_launch": bo,
                 "mean_staleness": ro["sigma_mean"]}
+    if not args.no_extra:
+        # 54 learners, 1-softsync (the shape of the paper's Rudra-adv ImageNet run, Table 4): flat, and as a tree with nodes of 3
+        from dataclasses import replace
+        w54 = replace(configs.C4, name="C4-54-learners-flat", n_learners=54)
+        rf = run_gpu(w54, 60, 5, ring=args.ring, flags=base_flags, **launch)
+        bf = algorithmic_bytes_per_update(w54)
+        line["extra"][w54.name] = {"applyUpdates_per_s": rf["updates"] / rf["wall_s"], "avg_launch_ms": rf["event_ms"] / rf["updates"],
+                                   "absorbed_gradient_GBps": rf["pushes"] * 4 * w54.n_params / rf["wall_s"] / 1e9,
+                                   "achieved_GBps": bf / (rf["event_ms"] / rf["updates"] * 1e-3) / 1e9, "bytes_per_launch": bf}
+        rt3 = run_gpu_tree(w54, 3, 60, 5, ring=args.ring)
+        # per update: 18 node launches of (3 reads + 1 write) and the root launch over 18 relayed averages + theta, v
+        bt = w54.n_params * ((w54.c // 3) * 16 + 4 * (w54.c // 3) + 16)
+        line["extra"]["C4-54-learners-tree-of-3"] = {
+            "applyUpdates_per_s": rt3["updates"] / rt3["wall_s"], "ms_per_update": rt3["event_ms"] / rt3["updates"],
+            "absorbed_gradient_GBps": rt3["pushes"] * 4 * w54.n_params / rt3["wall_s"] / 1e9,
+            "achieved_GBps": bt / (rt3["event_ms"] / rt3["updates"] * 1e-3) / 1e9, "bytes_per_update": bt,
+            "launches_per_update": w54.c // 3 + 1}
     if not args.no_cpu_baseline:
         cb = run_cpu_oracle(w)
         line["cpu_baseline"] = {"value": cb["value"], "unit": "applyUpdates/s", "cores": 1, "kind": "oracle",

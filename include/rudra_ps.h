@@ -109,6 +109,9 @@ typedef struct {
   uint32_t launch_waves_per_cu; /* cap on resident wavefronts per compute unit, 2..32 (enforced by reserving LDS per
                                    workgroup); 0 = library default.  Fewer resident waves keep fewer DRAM pages open
                                    at once; see the kernel header for the measured optimum. */
+  uint32_t max_aggregate;    /* largest number of learner gradients one rudra_ps_push_aggregate message may stand for
+                                (0 or 1: relayed averages are not used).  An update can then collect up to
+                                c + max_aggregate - 1 gradients. */
   uint32_t launch_alternate; /* 1: successive updates walk the vector in opposite directions, so the theta/v lines
                                 written last are the first read next (memory-side cache reuse); 2: always forward;
                                 0 = library default (alternate) */
@@ -172,6 +175,21 @@ int rudra_ps_destroy(rudra_ps_t* ps);
  * Errors: EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, EHIP. */
 int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out);
 
+/* The root of a parameter-server tree (Sec. 3.3) receiving what a node relays: avg = the average of m learner
+ * gradients (see rudra_ps_leaf_mean), with the m timestamps of those gradients (HOST pointer ts) so that staleness,
+ * vector clock and <sigma> stay exact.  It counts as m gradients: the running sum takes m*avg, applyUpdate fires once
+ * at least c gradients are in ("at least c", Sec. 3.1) and averages over the number collected.  The paper does not
+ * say which timestamp a relayed average carries nor when a node relays: this is this library's reading.
+ * avg: DEVICE pointer, borrowed like a pushed gradient.  out->staleness = the largest constituent staleness.
+ * Errors: EINVAL (m = 0, m > max_aggregate, RUDRA_LR_PER_GRADIENT, bad pointer), EFUTURE_TS, EHARDSYNC_STALE, EHIP. */
+int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts, uint32_t m, rudra_push_result_t* out);
+
+/* The arithmetic of a non-root node of the tree (Sec. 3.3: it averages the gradients sent from its learners and relays
+ * the average): out[i] = (g_1[i] + ... + g_k[i]) * (1/k), added in the order given.  grads: HOST array of k DEVICE
+ * pointers (P floats each, 16-byte aligned, read once); out: DEVICE pointer to P floats; enqueued on `stream` of
+ * `device`.  Stateless: which gradients form a group, and their timestamps, are the caller's (the transport's). */
+int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params, float* out, int32_t device, void* stream);
+
 /* pullWeights (Sec. 2, Sec. 3.2 "Learner"): the weights and their timestamp.  dst: DEVICE pointer to P floats
  * receiving a copy enqueued on the stream after all updates so far, or NULL for the timestamp inquiry a learner
  * makes first to skip the transfer.  ts_out: HOST pointer, may be NULL. */
@@ -197,8 +215,8 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out);
 int rudra_ps_staleness_hist(rudra_ps_t* ps, uint64_t* out, uint64_t cap, uint64_t* n_out);
 
 /* Vector clock of update `update_idx` (0-based: the update advancing timestamp update_idx -> update_idx+1): the c
- * gradient timestamps in arrival order, its <sigma> (Eq. 2) and its learning rate.  HOST pointers; avg_sigma_out and
- * lr_out may be NULL.  ERANGE if the update has not happened, has left the ring, or cap < c. */
+ * gradient timestamps in arrival order (n_out of them: c, or up to c + max_aggregate - 1), its <sigma> (Eq. 2) and its learning rate.  HOST pointers; avg_sigma_out and
+ * lr_out may be NULL.  ERANGE if the update has not happened, has left the ring, or cap < n_out. */
 int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out, uint32_t cap, uint32_t* n_out,
                           double* avg_sigma_out, float* lr_out);
 

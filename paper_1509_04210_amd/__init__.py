@@ -6,5 +6,5 @@ without the built library raises.
 """
 from .binding import (  # noqa: F401
     FLAG_CHECK_POINTERS, FLAG_CONTROL_ONLY, FLAG_DOUBLE_BUFFER, FLAG_PUSH_ACCUMULATE, FLAG_STATS_NORMS, FLAG_TIME_KERNELS, HARDSYNC, LR_AVG_STALENESS,
-    LR_CONST, LR_PER_GRADIENT, LR_STATIC_N, OPT_ADAGRAD, OPT_SGD, SOFTSYNC, ParameterServer, PushResult, RudraError, Stats, lib,
+    LR_CONST, LR_PER_GRADIENT, LR_STATIC_N, OPT_ADAGRAD, OPT_SGD, SOFTSYNC, ParameterServer, PushResult, RudraError, Stats, leaf_mean, lib,
     strerror)

@@ -27,7 +27,7 @@ class Config(C.Structure):
                 ("weight_decay", C.c_float), ("optimizer", C.c_int32), ("adagrad_eps", C.c_float), ("device", C.c_int32), ("flags", C.c_uint32),
                 ("stream", C.c_void_p), ("clock_ring", C.c_uint32), ("launch_block", C.c_uint32),
                 ("launch_unroll", C.c_uint32), ("launch_vec", C.c_uint32), ("launch_grid", C.c_uint32),
-                ("launch_waves_per_cu", C.c_uint32), ("launch_alternate", C.c_uint32)]
+                ("launch_waves_per_cu", C.c_uint32), ("max_aggregate", C.c_uint32), ("launch_alternate", C.c_uint32)]
 
 
 class PushResult(C.Structure):
@@ -63,6 +63,8 @@ def lib():
             "rudra_ps_create": [C.POINTER(Config), vp, C.POINTER(vp)],
             "rudra_ps_destroy": [vp],
             "rudra_ps_push_gradient": [vp, vp, u64, i32, C.POINTER(PushResult)],
+            "rudra_ps_push_aggregate": [vp, vp, C.POINTER(u64), u32, C.POINTER(PushResult)],
+            "rudra_ps_leaf_mean": [C.POINTER(vp), u32, u64, vp, i32, vp],
             "rudra_ps_pull_weights": [vp, vp, C.POINTER(u64)],
             "rudra_ps_weights_view": [vp, C.POINTER(vp), C.POINTER(u64)],
             "rudra_ps_pull_velocity": [vp, vp],
@@ -91,6 +93,14 @@ class RudraError(RuntimeError):
         self.status = status
 
 
+def leaf_mean(grad_ptrs, n_params, out_ptr, device=0, stream=0):
+    """rudra_ps_leaf_mean: out = (g_1 + ... + g_k) * (1/k) on the device."""
+    arr = (C.c_void_p * len(grad_ptrs))(*grad_ptrs)
+    rc = lib().rudra_ps_leaf_mean(arr, len(grad_ptrs), n_params, out_ptr, device, stream or None)
+    if rc != OK:
+        raise RudraError(rc, "rudra_ps_leaf_mean")
+
+
 class ParameterServer:
     """One rudra_ps_t.  Methods return the C status where a caller may want to see a rejection
     (push_gradient) and raise RudraError otherwise."""
@@ -99,11 +109,11 @@ class ParameterServer:
                  lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0, weight_decay=0.0,
                  c_override=0, device=0, stream=0, flags=0, clock_ring=0, launch_block=0, launch_unroll=0,
                  launch_vec=0, launch_grid=0, launch_waves_per_cu=0, launch_alternate=0, optimizer=OPT_SGD,
-                 adagrad_eps=1e-8):
+                 adagrad_eps=1e-8, max_aggregate=0):
         self._L = lib()
         self.cfg = Config(n_params, n_learners, n_split, c_override, protocol, lr_mode, alpha0, lr_scale, momentum,
                           weight_decay, optimizer, adagrad_eps, device, flags, stream or None, clock_ring, launch_block, launch_unroll,
-                          launch_vec, launch_grid, launch_waves_per_cu, launch_alternate)
+                          launch_vec, launch_grid, launch_waves_per_cu, max_aggregate, launch_alternate)
         h = C.c_void_p()
         rc = self._L.rudra_ps_create(C.byref(self.cfg), init_weights_ptr or None, C.byref(h))
         if rc != OK:
@@ -122,6 +132,12 @@ class ParameterServer:
     def push_gradient(self, grad_ptr, ts, learner=-1):
         """(status, PushResult).  The PushResult object is reused by the next call."""
         rc = self._L.rudra_ps_push_gradient(self._h, grad_ptr or None, ts, learner, C.byref(self._res))
+        return rc, self._res
+
+    def push_aggregate(self, avg_ptr, ts_list):
+        """A relayed average standing for len(ts_list) learner gradients.  (status, PushResult)."""
+        ts = (C.c_uint64 * len(ts_list))(*ts_list)
+        rc = self._L.rudra_ps_push_aggregate(self._h, avg_ptr or None, ts, len(ts_list), C.byref(self._res))
         return rc, self._res
 
     def pull_weights(self, dst_ptr=0):
@@ -163,10 +179,10 @@ class ParameterServer:
 
     def vector_clock(self, update_idx):
         """(timestamps, <sigma>, lr) of one update; raises RudraError(ERANGE) if it left the ring."""
-        c = self.stats().c
-        buf = (C.c_uint64 * c)()
+        cap = self.stats().c + self.cfg.max_aggregate       # an update collects at most c + max_aggregate - 1 gradients
+        buf = (C.c_uint64 * cap)()
         n, avg, lr = C.c_uint32(), C.c_double(), C.c_float()
-        rc = self._L.rudra_ps_vector_clock(self._h, update_idx, buf, c, C.byref(n), C.byref(avg), C.byref(lr))
+        rc = self._L.rudra_ps_vector_clock(self._h, update_idx, buf, cap, C.byref(n), C.byref(avg), C.byref(lr))
         if rc != OK:
             raise RudraError(rc, "rudra_ps_vector_clock")
         return list(buf[:n.value]), avg.value, lr.value

@@ -263,7 +263,9 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 // sumGradients alone: sum_out[k] = w_1*g_1[k] + ... in arrival order.  Used when a gradient is
 // accumulated at push time and to fold sets of more than kMaxFused gradients; sum_out may be
 // the same buffer as gs.p[0] (each position is read, then written, by one lane).
-template <bool WEIGHTED, int U, int V>
+// With SCALE the sum is multiplied by a.inv_c before it is stored: the average a node of the server tree relays
+// to its parent (Sec. 3.3).
+template <bool WEIGHTED, bool SCALE, int U, int V>
 __global__ void sum_gradients_kernel(const GradSet gs, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t tile = (uint64_t)blockDim.x * V;
@@ -276,12 +278,17 @@ __global__ void sum_gradients_kernel(const GradSet gs, const UpdateArgs a) {
       if (i1[0] >= n4) break;
       floatx4 s[1];
       sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
+      if (SCALE) s[0] = s[0] * a.inv_c;
       store_state4(out4, i1[0], s[0]);
     }
   }
   if (blockIdx.x == 0) {
     const uint64_t k = (n4 << 2) + threadIdx.x;
-    if (k < a.n_params) a.sum_out[k] = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
+    if (k < a.n_params) {
+      float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
+      if (SCALE) s = s * a.inv_c;
+      a.sum_out[k] = s;
+    }
   }
 }
 

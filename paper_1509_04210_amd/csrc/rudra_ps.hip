@@ -63,13 +63,16 @@ struct rudra_ps {
   uint64_t ts_cur = 0;
   uint32_t count = 0;
   uint64_t sigma_sum_open = 0;
-  std::vector<uint64_t> open_clock;
+  std::vector<uint64_t> open_clock;  // clock_cap entries
+  uint32_t clock_cap = 0;            // c + max_aggregate - 1
+  bool open_weighted = false;        // some pending message has a weight other than 1
   std::vector<Pending> open_grads;
   std::vector<uint8_t> seen;
 
   // closed clocks (ring over update index)
   uint32_t ring = kDefaultClockRing;
   std::vector<uint64_t> ring_ts;
+  std::vector<uint32_t> ring_count;
   std::vector<double> ring_avg;
   std::vector<float> ring_lr;
 
@@ -187,13 +190,13 @@ void launch_apply(int opt, bool decay, bool weighted, bool stats, uint32_t unrol
 void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   // the fold/accumulate path is not the measured one: a single shape (4 loads in flight)
   if (weighted) {
-    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
-    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
-    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, false, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, false, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<true, false, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
   } else {
-    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
-    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
-    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    if (vec == 1) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else if (vec == 2) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
   }
 }
 
@@ -247,7 +250,7 @@ int resolve_timer(rudra_ps* ps, uint64_t launch_idx) {
 // sumGradients + applyUpdate for the c pending gradients (Eq. 3 / Eq. 5), one fused launch
 // when c <= kMaxFused.
 int enqueue_update(rudra_ps* ps, float lr) {
-  const bool weighted = ps->cfg.lr_mode == RUDRA_LR_PER_GRADIENT;
+  const bool weighted = ps->open_weighted;
   std::vector<Pending>& g = ps->open_grads;
   size_t first = 0;
   Pending head = {nullptr, 1.0f};
@@ -273,7 +276,8 @@ int enqueue_update(rudra_ps* ps, float lr) {
 
   UpdateArgs a = base_args(ps);
   a.c = n;
-  a.inv_c = 1.0f / (float)ps->c;  // Eq. 5: the mean is over all c gradients of the update
+  a.inv_c = 1.0f / (float)ps->count;  // Eq. 5: the mean is over all gradients of the update (c of them, unless a
+                                      // relayed average made the count overshoot)
   a.lr = lr;
   a.reverse = (ps->alternate && (ps->n_updates & 1)) ? 1u : 0u;
   const LaunchShape s = shape_for(ps);
@@ -337,6 +341,8 @@ int validate_config(const rudra_ps_config_t* c) {
     return RUDRA_EINVAL;
   if (c->launch_vec && c->launch_vec != 1 && c->launch_vec != 2 && c->launch_vec != 4) return RUDRA_EINVAL;
   if (c->launch_alternate > 2) return RUDRA_EINVAL;
+  if (c->max_aggregate > 1 && c->lr_mode == RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;  // a relayed average cannot be re-weighted
+  if (c->max_aggregate > 4096) return RUDRA_EINVAL;
   if (c->launch_waves_per_cu && (c->launch_waves_per_cu < 2 || c->launch_waves_per_cu > 32)) return RUDRA_EINVAL;
   if ((c->launch_unroll ? c->launch_unroll : kDefaultUnroll) * (c->launch_vec ? c->launch_vec : kDefaultVec) > 8)
     return RUDRA_EINVAL;  // more 16-byte loads per lane than the register file holds without spilling
@@ -409,10 +415,12 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   }
   ps->ring = config->clock_ring ? config->clock_ring : kDefaultClockRing;
   try {
-    ps->open_clock.assign(ps->c, 0);
+    ps->clock_cap = ps->c + (config->max_aggregate > 1 ? config->max_aggregate - 1 : 0);
+    ps->open_clock.assign(ps->clock_cap, 0);
     ps->open_grads.reserve(ps->c);
     ps->seen.assign(config->n_learners, 0);
-    ps->ring_ts.assign((size_t)ps->ring * ps->c, 0);
+    ps->ring_ts.assign((size_t)ps->ring * ps->clock_cap, 0);
+    ps->ring_count.assign(ps->ring, 0);
     ps->ring_avg.assign(ps->ring, 0.0);
     ps->ring_lr.assign(ps->ring, 0.f);
     ps->hist.reserve(64);
@@ -460,50 +468,38 @@ int rudra_ps_destroy(rudra_ps_t* ps) {
   return RUDRA_OK;
 }
 
-int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
-  if (!ps) return RUDRA_EINVAL;
-  std::lock_guard<std::mutex> lock(ps->mu);
-  if (ps->failed) return RUDRA_EHIP;
+// A message (one gradient, or a relayed average standing for m of them) that has passed validation: sumGradients
+// bookkeeping, vector clock, and applyUpdate once at least c gradients are in.  Caller holds the mutex.
+static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t m, int32_t learner, float weight,
+                  rudra_push_result_t* out) {
   const rudra_ps_config_t& cfg = ps->cfg;
-  // ---- validation: a rejected message changes nothing but the rejection counter ----
-  if (!ps->control_only && (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u))) { ps->n_rejected++; return RUDRA_EINVAL; }
-  if (learner < -1 || learner >= (int32_t)cfg.n_learners) { ps->n_rejected++; return RUDRA_EINVAL; }
-  if (ps->check_pointers) {
-    if (hipSetDevice(cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
-    if (!is_device_range(grad, cfg.n_params * sizeof(float), cfg.device)) { ps->n_rejected++; return RUDRA_EINVAL; }
-  }
-  if (ts > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
-  if (cfg.protocol == RUDRA_HARDSYNC) {
-    if (ts != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }
-    if (learner >= 0 && ps->seen[learner]) { ps->n_rejected++; return RUDRA_EHARDSYNC_DUP; }
-  }
-  // ---- staleness and vector clock (Sec. 3.1) ----
-  const uint64_t sigma = ps->ts_cur - ts;
-  float weight = 1.0f;
-  if (cfg.lr_mode == RUDRA_LR_PER_GRADIENT) weight = (float)(1.0 / (sigma > 1 ? (double)sigma : 1.0));
-
   if (!ps->control_only) {
     if (hipSetDevice(cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
     if (ps->accumulate) {  // sumGradients at arrival: acc = w*g, or acc = acc + w*g
-      const bool weighted = cfg.lr_mode == RUDRA_LR_PER_GRADIENT;
+      const bool weighted = weight != 1.0f || ps->open_weighted;
       Pending two[2] = {{ps->acc, 1.0f}, {grad, weight}};
       int rc = (ps->count == 0) ? enqueue_sum(ps, two + 1, 1, weighted) : enqueue_sum(ps, two, 2, weighted);
       if (rc != RUDRA_OK) return rc;
     }
   }
-  count_staleness(ps, sigma);
-  ps->open_clock[ps->count] = ts;
+  uint64_t worst = 0;
+  for (uint32_t j = 0; j < m; ++j) {  // staleness and vector clock (Sec. 3.1), one entry per learner gradient
+    const uint64_t sigma = ps->ts_cur - ts[j];
+    worst = std::max(worst, sigma);
+    count_staleness(ps, sigma);
+    ps->open_clock[ps->count++] = ts[j];
+    ps->sigma_sum_open += sigma;
+  }
+  ps->n_pushes += m;
+  if (weight != 1.0f) ps->open_weighted = true;
   if (!ps->accumulate) ps->open_grads.push_back({grad, weight});
-  ps->count += 1;
-  ps->sigma_sum_open += sigma;
-  ps->n_pushes += 1;
   if (learner >= 0 && cfg.protocol == RUDRA_HARDSYNC) ps->seen[learner] = 1;
 
   int applied = 0;
   float lr_used = 0.f;
-  if (ps->count == ps->c) {
+  if (ps->count >= ps->c) {  // "at least c gradients": exactly c unless a relayed average overshoots
     // <sigma> of this update: mean over its clock of (ts_cur - ts_k) = (i-1) - mean(i_k), Eq. 2
-    const double avg_sigma = (double)ps->sigma_sum_open / (double)ps->c;
+    const double avg_sigma = (double)ps->sigma_sum_open / (double)ps->count;
     double lr = (double)cfg.alpha0 * (double)cfg.lr_scale;
     if (cfg.lr_mode == RUDRA_LR_STATIC_N) lr = lr / (double)cfg.n_split;
     else if (cfg.lr_mode == RUDRA_LR_AVG_STALENESS) lr = lr / (avg_sigma > 1.0 ? avg_sigma : 1.0);
@@ -517,7 +513,8 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
       if (rc != RUDRA_OK) { ps->failed = true; return rc; }
     }
     const size_t slot = (size_t)(ps->n_updates % ps->ring);
-    std::copy(ps->open_clock.begin(), ps->open_clock.end(), ps->ring_ts.begin() + slot * ps->c);
+    std::copy(ps->open_clock.begin(), ps->open_clock.begin() + ps->count, ps->ring_ts.begin() + slot * ps->clock_cap);
+    ps->ring_count[slot] = ps->count;
     ps->ring_avg[slot] = avg_sigma;
     ps->ring_lr[slot] = lr_used;
     ps->last_avg = avg_sigma;
@@ -526,16 +523,104 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
     ps->ts_cur += 1;  // each weight update increments the timestamp
     ps->count = 0;
     ps->sigma_sum_open = 0;
+    ps->open_weighted = false;
     ps->open_grads.clear();
     std::fill(ps->seen.begin(), ps->seen.end(), 0);
     applied = 1;
   }
   if (out) {
-    out->staleness = sigma;
+    out->staleness = worst;
     out->ts_after = ps->ts_cur;
     out->pending = ps->count;
     out->applied = applied;
     out->lr_used = lr_used;
+  }
+  return RUDRA_OK;
+}
+
+// null / alignment / (optionally) runtime check of a pushed device pointer
+static int check_pushed_pointer(rudra_ps* ps, const float* grad) {
+  if (ps->control_only) return RUDRA_OK;
+  if (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u)) return RUDRA_EINVAL;
+  if (ps->check_pointers) {
+    if (hipSetDevice(ps->cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
+    if (!is_device_range(grad, ps->cfg.n_params * sizeof(float), ps->cfg.device)) return RUDRA_EINVAL;
+  }
+  return RUDRA_OK;
+}
+
+int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->failed) return RUDRA_EHIP;
+  const rudra_ps_config_t& cfg = ps->cfg;
+  // ---- validation: a rejected message changes nothing but the rejection counter ----
+  int rc = check_pushed_pointer(ps, grad);
+  if (rc == RUDRA_EHIP) return rc;
+  if (rc != RUDRA_OK) { ps->n_rejected++; return rc; }
+  if (learner < -1 || learner >= (int32_t)cfg.n_learners) { ps->n_rejected++; return RUDRA_EINVAL; }
+  if (ts > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
+  if (cfg.protocol == RUDRA_HARDSYNC) {
+    if (ts != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }
+    if (learner >= 0 && ps->seen[learner]) { ps->n_rejected++; return RUDRA_EHARDSYNC_DUP; }
+  }
+  const uint64_t sigma = ps->ts_cur - ts;
+  float weight = 1.0f;
+  if (cfg.lr_mode == RUDRA_LR_PER_GRADIENT) {  // Sec. 5.1 footnote: a staler gradient gets a smaller rate
+    weight = (float)(1.0 / (sigma > 1 ? (double)sigma : 1.0));
+    ps->open_weighted = true;  // every update of this mode runs the weighted kernel
+  }
+  return absorb(ps, grad, &ts, 1, learner, weight, out);
+}
+
+int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts, uint32_t m, rudra_push_result_t* out) {
+  if (!ps || !ts || m == 0) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->failed) return RUDRA_EHIP;
+  const rudra_ps_config_t& cfg = ps->cfg;
+  int rc = check_pushed_pointer(ps, avg);
+  if (rc == RUDRA_EHIP) return rc;
+  if (rc != RUDRA_OK) { ps->n_rejected++; return rc; }
+  const uint32_t max_m = cfg.max_aggregate > 1 ? cfg.max_aggregate : 1;
+  if (m > max_m || cfg.lr_mode == RUDRA_LR_PER_GRADIENT) { ps->n_rejected++; return RUDRA_EINVAL; }
+  for (uint32_t j = 0; j < m; ++j) {
+    if (ts[j] > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
+    if (cfg.protocol == RUDRA_HARDSYNC && ts[j] != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }
+  }
+  // the message stands for m learner gradients: the running sum takes m * avg
+  return absorb(ps, avg, ts, m, -1, (float)m, out);
+}
+
+int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params, float* out, int32_t device, void* stream) {
+  if (!grads || !out || k == 0 || n_params == 0 || (reinterpret_cast<uintptr_t>(out) & 15u)) return RUDRA_EINVAL;
+  for (uint32_t j = 0; j < k; ++j)
+    if (!grads[j] || (reinterpret_cast<uintptr_t>(grads[j]) & 15u)) return RUDRA_EINVAL;
+  if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return RUDRA_EHIP; }
+  const uint64_t n4 = n_params >> 2;
+  const uint32_t block = kDefaultBlock;
+  const uint64_t tiles = (n4 + block - 1) / block;
+  uint64_t grid = tiles ? tiles : 1;
+  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
+  const LaunchShape shape = {(uint32_t)grid, block, tiles, 0};
+  UpdateArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.sum_out = out;
+  a.n_params = n_params;
+  a.ntiles = tiles;
+  uint32_t first = 0;
+  bool have_head = false;
+  while (first < k) {  // groups of at most kMaxFused pointers; the running sum continues through `out`
+    GradSet gs;
+    std::memset(&gs, 0, sizeof(gs));
+    uint32_t n = 0;
+    if (have_head) { gs.p[n] = out; gs.w[n] = 1.0f; ++n; }
+    while (n < (uint32_t)kMaxFused && first < k) { gs.p[n] = grads[first++]; gs.w[n] = 1.0f; ++n; }
+    a.c = n;
+    a.inv_c = (first == k) ? 1.0f / (float)k : 1.0f;  // (g_1 + ... + g_k) * (1/k): scaled once, at the end
+    if (first == k) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, true, 4, 1>), dim3(shape.grid), dim3(shape.block), 0, (hipStream_t)stream, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 1>), dim3(shape.grid), dim3(shape.block), 0, (hipStream_t)stream, gs, a);
+    if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
+    have_head = true;
   }
   return RUDRA_OK;
 }
@@ -641,9 +726,12 @@ int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out,
   if (!ps || !ts_out) return RUDRA_EINVAL;
   std::lock_guard<std::mutex> lock(ps->mu);
   if (n_out) *n_out = ps->c;
-  if (update_idx >= ps->n_updates || ps->n_updates - update_idx > ps->ring || cap < ps->c) return RUDRA_ERANGE;
+  if (update_idx >= ps->n_updates || ps->n_updates - update_idx > ps->ring) return RUDRA_ERANGE;
   const size_t slot = (size_t)(update_idx % ps->ring);
-  std::memcpy(ts_out, ps->ring_ts.data() + slot * ps->c, ps->c * sizeof(uint64_t));
+  const uint32_t n = ps->ring_count[slot];
+  if (n_out) *n_out = n;
+  if (cap < n) return RUDRA_ERANGE;
+  std::memcpy(ts_out, ps->ring_ts.data() + slot * ps->clock_cap, n * sizeof(uint64_t));
   if (avg_sigma_out) *avg_sigma_out = ps->ring_avg[slot];
   if (lr_out) *lr_out = ps->ring_lr[slot];
   return RUDRA_OK;

@@ -28,7 +28,7 @@ class HipServer:
     consumed it was enqueued on the same stream.
     """
 
-    def __init__(self, workload, flags=0, device=0, ring=None, pregenerated=0, **launch):
+    def __init__(self, workload, flags=0, device=0, ring=None, pregenerated=0, avg_ring=0, **launch):
         self.w = workload
         self.dev = torch.device("cuda", device)
         self.stream = torch.cuda.Stream(device=self.dev)
@@ -44,6 +44,9 @@ class HipServer:
                                     workload.lr_scale, workload.momentum, workload.weight_decay,
                                     workload.c_override, device, self.sh, flags, optimizer=OPTIMIZER[workload.optimizer],
                                     adagrad_eps=workload.adagrad_eps, **launch)
+        # tree mode: buffers for relayed averages (borrowed by the root until its update has run)
+        self.avg_ring = [torch.empty(P, dtype=torch.float32, device=self.dev) for _ in range(avg_ring)]
+        self._next_avg = 0
         self.pregenerated = pregenerated
         for i in range(pregenerated):
             self._fill(self.ring[i], i % workload.n_learners, i // workload.n_learners)
@@ -62,6 +65,21 @@ class HipServer:
         if not self.pregenerated:
             self._fill(buf, learner, step)
         rc, res = self.ps.push_gradient(buf.data_ptr(), ts, learner)
+        return rc, res.staleness, res.applied
+
+    def push_aggregate(self, members, ts_list):
+        """A tree node's work for `members` = [(learner, step), ...]: materialise their gradients, average them on the
+        device (rudra_ps_leaf_mean) and relay the average with the members' timestamps to the root."""
+        ptrs = []
+        for l, s in members:
+            buf = self.ring[self._next]
+            self._next = (self._next + 1) % len(self.ring)
+            self._fill(buf, l, s)
+            ptrs.append(buf.data_ptr())
+        avg = self.avg_ring[self._next_avg]
+        self._next_avg = (self._next_avg + 1) % len(self.avg_ring)
+        B.leaf_mean(ptrs, self.w.n_params, avg.data_ptr(), self.dev.index or 0, self.sh)
+        rc, res = self.ps.push_aggregate(avg.data_ptr(), ts_list)
         return rc, res.staleness, res.applied
 
     def pull_ts(self):

@@ -40,3 +40,35 @@ def replay(server, learner, step, n_learners, hardsync=False):
         else:
             learner_ts[l] = now
     return log
+
+
+def replay_tree(server, learner, step, n_learners, fan_in, hardsync=False):
+    """The same learners under a two-level server tree (Sec. 3.3): learner l talks to node l // fan_in; a node relays
+    the average of every `fan_in` gradients it has received (in arrival order) to the root.  `server` needs
+        push_aggregate(members, ts_list) -> (rc, staleness, applied)      # members: [(learner, step), ...]
+        pull_ts() -> int
+    A learner pulls right after handing its gradient to its node (weights travel down the tree at no cost here).
+    Returns per-message logs (one entry per relayed average) and what was left waiting in the nodes."""
+    n_nodes = -(-n_learners // fan_in)
+    waiting = [[] for _ in range(n_nodes)]
+    learner_ts = np.zeros(n_learners, dtype=np.int64)
+    log = dict(staleness=[], applied=[], ts_at_arrival=[], size=[])
+    for i in range(len(learner)):
+        l, s = int(learner[i]), int(step[i])
+        node = waiting[l // fan_in]
+        node.append((l, s, int(learner_ts[l])))
+        if len(node) == fan_in:
+            log["ts_at_arrival"].append(server.pull_ts())
+            rc, sigma, applied = server.push_aggregate([(a, b) for a, b, _ in node], [t for _, _, t in node])
+            if rc != 0:
+                raise RuntimeError(f"relayed message at push {i} rejected: {rc}")
+            log["staleness"].append(sigma)
+            log["applied"].append(applied)
+            log["size"].append(fan_in)
+            node.clear()
+            if hardsync and applied:
+                learner_ts[:] = server.pull_ts()      # the new weights are broadcast to every learner
+        learner_ts[l] = server.pull_ts()
+    out = {k: np.array(v, dtype=np.int64) for k, v in log.items()}
+    out["left_in_nodes"] = sum(len(n) for n in waiting)
+    return out

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in include/rudra_ps.h but not exported"
-    assert len(declared) == 12
+    assert len(declared) == 14
 
 
 def test_struct_layouts_match_the_header():

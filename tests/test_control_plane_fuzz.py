@@ -20,20 +20,27 @@ def test_random_message_sequences(lam, data):
     hard = data.draw(st.booleans())
     n = 1 if hard else data.draw(st.integers(1, lam))
     c_override = data.draw(st.sampled_from([0, 0, 0, 1, 3, 11]))
-    lr_mode = data.draw(st.sampled_from(LR_MODES))
+    max_agg = data.draw(st.sampled_from([0, 0, 1, 2, 5]))
+    lr_mode = data.draw(st.sampled_from(LR_MODES if max_agg <= 1 else LR_MODES[:3]))
     alpha0 = data.draw(st.sampled_from([0.5, 0.01, 0.3]))
     lr_scale = data.draw(st.sampled_from([1.0, 0.96875]))
     proto = oracle.HARDSYNC if hard else oracle.SOFTSYNC
     ps = R.ParameterServer(3, lam, 0, n, proto, lr_mode, alpha0, lr_scale, c_override=c_override,
-                           flags=B.FLAG_CONTROL_ONLY, clock_ring=4096)
-    ora = OraclePS(np.zeros(3, np.float32), lam, n, proto, lr_mode, alpha0, lr_scale, c_override=c_override)
+                           flags=B.FLAG_CONTROL_ONLY, clock_ring=4096, max_aggregate=max_agg)
+    ora = OraclePS(np.zeros(3, np.float32), lam, n, proto, lr_mode, alpha0, lr_scale, c_override=c_override,
+                   max_aggregate=max_agg)
     g = np.ones(3, np.float32)
     for _ in range(data.draw(st.integers(1, 80))):
         # timestamps around the current one (past, present, future), learners around the valid range
         ts = max(0, ora.ts + data.draw(st.integers(-4, 1)))
         learner = data.draw(st.integers(-2, lam))
-        rc_h, r = ps.push_gradient(0, ts, learner)
-        rc_o, ro = ora.push(g, ts, learner)
+        if data.draw(st.integers(0, 3)) == 0:      # a relayed average of 1..max+1 gradients (one too many is rejected)
+            stamps = [max(0, ora.ts + data.draw(st.integers(-3, 1))) for _ in range(data.draw(st.integers(1, max(1, max_agg) + 1)))]
+            rc_h, r = ps.push_aggregate(0, stamps)
+            rc_o, ro = ora.push_aggregate(g, stamps)
+        else:
+            rc_h, r = ps.push_gradient(0, ts, learner)
+            rc_o, ro = ora.push(g, ts, learner)
         assert rc_h == rc_o
         if rc_h == 0:
             assert (r.staleness, r.ts_after, r.pending, r.applied, np.float32(r.lr_used)) == \
@@ -46,7 +53,7 @@ def test_random_message_sequences(lam, data):
     clocks, avg, lr = ora.clocks, ora.avg_staleness, ora.lr_log
     for u in range(ora.n_updates):
         t, a, r = ps.vector_clock(u)
-        assert t == list(clocks[u]) and a == avg[u] and np.float32(r) == lr[u]
+        assert t == [int(x) for x in clocks[u]] and a == avg[u] and np.float32(r) == lr[u]
 
 
 def test_concurrent_pushes_are_serialised():

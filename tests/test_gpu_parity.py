@@ -394,3 +394,74 @@ def test_pointer_check_rejects_what_a_kernel_would_fault_on(hipmod):
         B.ParameterServer(10_000, 2, host_ptr)
     assert e.value.status == B.EINVAL
     hip.close()
+
+
+# ---------------------------------------------------------------- parameter-server tree (Sec. 3.3)
+@pytest.mark.parametrize("k,n", [(1, 1000), (2, 4099), (3, 70_001), (7, 5), (18, 33_333), (64, 2050), (65, 2051), (130, 777)])
+def test_leaf_mean_kernel(hipmod, k, n):
+    """rudra_ps_leaf_mean == the oracle's node average, bit for bit (groups beyond 64 gradients are folded)."""
+    import oracle
+    from paper_1509_04210_amd import binding as B
+    key = lambda j: gradgen.stream_key(5, gradgen.TAG_GRAD, j, n)
+    bufs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(k)]
+    out = torch.full((n + 8,), 9.0, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    for j, b in enumerate(bufs):
+        gradgen.fill_device(b.data_ptr(), n, key(j), 1e-3, 100, 100.0, stream=0)
+    B.leaf_mean([b.data_ptr() for b in bufs], n, out.data_ptr(), 0, 0)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = oracle.leaf_mean([gradgen.vector(key(j), n, 1e-3, 100, 100.0) for j in range(k)])
+    assert np.array_equal(got[:n], want) and np.all(got[n:] == 9.0)
+
+
+@pytest.mark.parametrize("name,lam,fan_in,n_split,P,n_pushes", [
+    ("C4", 54, 3, 1, 60_001, 54 * 6 + 10),        # the paper's Rudra-adv ImageNet run: 54 learners, 1-softsync, here nodes of 3
+    ("C5", 12, 4, 3, 30_002, 300),                # c = 4 = one relayed message per update
+    ("C4-adagrad", 10, 4, 1, 20_003, 200),        # 10 learners in nodes of 4, 4, 2 (the last node never fills): c = 10 is overshot
+    ("C2", 8, 2, 1, 10_001, 8 * 12),              # hardsync under a tree
+])
+def test_tree_parity(hipmod, name, lam, fan_in, n_split, P, n_pushes):
+    base = configs.ALL[name]
+    w = _with(base.scaled(n_params=P, n_pushes=n_pushes), n_learners=lam, n_split=n_split)
+    learner, step = w.arrival_trace()
+    hard = w.protocol == "hardsync"
+    hip = hipmod.HipServer(w, ring=2 * fan_in + 2, avg_ring=w.c // fan_in + 4, max_aggregate=fan_in)
+    ora = OracleServer(w, max_aggregate=fan_in)
+    lh = replay.replay_tree(hip, learner, step, lam, fan_in, hardsync=hard)
+    lo = replay.replay_tree(ora, learner, step, lam, fan_in, hardsync=hard)
+    for key in lo:
+        assert np.array_equal(lh[key], lo[key]), key
+    assert lo["applied"].sum() >= 3
+    th = hip.weights().cpu().numpy()
+    assert np.abs(th.astype(np.float64) - ora.ps.theta).max() <= TOL * np.abs(ora.ps.theta).max()
+    assert np.array_equal(th, ora.ps.theta)
+    if w.momentum != 0 or w.optimizer == "adagrad":
+        assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
+    st, o = hip.ps.stats(), ora.ps
+    assert (st.ts_cur, st.n_pushes, st.pending, st.sigma_sum, st.sigma_max) == (o.ts, o.n_pushes, o.pending, o.sigma_sum, o.sigma_max)
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), o.hist)
+    clocks, avg, lr = o.clocks, o.avg_staleness, o.lr_log
+    for u in range(o.n_updates):
+        t, a, r = hip.ps.vector_clock(u)
+        assert t == [int(x) for x in clocks[u]] and a == avg[u] and np.float32(r) == lr[u]
+    hip.close()
+
+
+def test_tree_full_size_on_sampled_elements(hipmod):
+    """72M parameters, 54 learners in 18 nodes of 3, 1-softsync (the shape of the paper's Rudra-adv ImageNet run)."""
+    lam, fan_in = 54, 3
+    w = _with(configs.C4.scaled(n_pushes=54 * 20), n_learners=lam)
+    idx = _sample_indices(w.n_params, 11, 8192)
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, ring=2 * fan_in + 2, avg_ring=w.c // fan_in + 4, max_aggregate=fan_in)
+    ora = OracleServer(w, index=idx, max_aggregate=fan_in)
+    lh = replay.replay_tree(hip, learner, step, lam, fan_in)
+    lo = replay.replay_tree(ora, learner, step, lam, fan_in)
+    for key in lo:
+        assert np.array_equal(lh[key], lo[key]), key
+    sel = torch.from_numpy(idx.astype(np.int64)).cuda()
+    assert np.array_equal(hip.weights()[sel].cpu().numpy(), ora.ps.theta)
+    assert np.array_equal(hip.velocity()[sel].cpu().numpy(), ora.ps.velocity)
+    assert hip.ps.stats().ts_cur == ora.ps.ts >= 19
+    hip.close()
