@@ -30,6 +30,31 @@ constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding l
 constexpr uint32_t kDefaultClockRing = 1024;
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
 
+// Makes `device` current for the calling thread and puts the previous one back on scope exit: a library call must
+// not leave the caller's thread on another device.
+class DeviceGuard {
+ public:
+  explicit DeviceGuard(int device) {  // device < 0: no device work in this call, touch nothing
+    if (device < 0) return;
+    err_ = hipGetDevice(&prev_);
+    if (err_ == hipSuccess && prev_ != device) {
+      err_ = hipSetDevice(device);
+      changed_ = err_ == hipSuccess;
+    }
+  }
+  ~DeviceGuard() {
+    if (changed_) (void)hipSetDevice(prev_);
+  }
+  DeviceGuard(const DeviceGuard&) = delete;
+  DeviceGuard& operator=(const DeviceGuard&) = delete;
+  hipError_t error() const { return err_; }
+
+ private:
+  int prev_ = 0;
+  bool changed_ = false;
+  hipError_t err_ = hipSuccess;
+};
+
 struct Pending {
   const float* ptr;
   float weight;
@@ -357,7 +382,7 @@ int validate_config(const rudra_ps_config_t* c) {
 
 void release(rudra_ps* ps) {
   if (!ps->control_only) {
-    (void)hipSetDevice(ps->cfg.device);
+    DeviceGuard guard(ps->cfg.device);
     (void)hipStreamSynchronize(ps->stream);
     for (hipEvent_t e : ps->ev_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : ps->ev_stop) (void)hipEventDestroy(e);
@@ -430,7 +455,8 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   }
   if (!control_only) {
     const size_t bytes = config->n_params * sizeof(float);
-    hipError_t e = hipSetDevice(config->device);
+    DeviceGuard guard(config->device);
+    hipError_t e = guard.error();
     if (e == hipSuccess && !is_device_range(init_weights, bytes, config->device)) {
       delete ps;
       return RUDRA_EINVAL;  // not P floats of this device's memory
@@ -474,7 +500,6 @@ static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t 
                   rudra_push_result_t* out) {
   const rudra_ps_config_t& cfg = ps->cfg;
   if (!ps->control_only) {
-    if (hipSetDevice(cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
     if (ps->accumulate) {  // sumGradients at arrival: acc = w*g, or acc = acc + w*g
       const bool weighted = weight != 1.0f || ps->open_weighted;
       Pending two[2] = {{ps->acc, 1.0f}, {grad, weight}};
@@ -543,7 +568,6 @@ static int check_pushed_pointer(rudra_ps* ps, const float* grad) {
   if (ps->control_only) return RUDRA_OK;
   if (!grad || (reinterpret_cast<uintptr_t>(grad) & 15u)) return RUDRA_EINVAL;
   if (ps->check_pointers) {
-    if (hipSetDevice(ps->cfg.device) != hipSuccess) return hip_fail(ps, hipGetLastError());
     if (!is_device_range(grad, ps->cfg.n_params * sizeof(float), ps->cfg.device)) return RUDRA_EINVAL;
   }
   return RUDRA_OK;
@@ -554,6 +578,8 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
   std::lock_guard<std::mutex> lock(ps->mu);
   if (ps->failed) return RUDRA_EHIP;
   const rudra_ps_config_t& cfg = ps->cfg;
+  DeviceGuard guard(ps->control_only ? -1 : cfg.device);
+  if (guard.error() != hipSuccess) return hip_fail(ps, guard.error());
   // ---- validation: a rejected message changes nothing but the rejection counter ----
   int rc = check_pushed_pointer(ps, grad);
   if (rc == RUDRA_EHIP) return rc;
@@ -578,6 +604,8 @@ int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts
   std::lock_guard<std::mutex> lock(ps->mu);
   if (ps->failed) return RUDRA_EHIP;
   const rudra_ps_config_t& cfg = ps->cfg;
+  DeviceGuard guard(ps->control_only ? -1 : cfg.device);
+  if (guard.error() != hipSuccess) return hip_fail(ps, guard.error());
   int rc = check_pushed_pointer(ps, avg);
   if (rc == RUDRA_EHIP) return rc;
   if (rc != RUDRA_OK) { ps->n_rejected++; return rc; }
@@ -595,7 +623,8 @@ int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params,
   if (!grads || !out || k == 0 || n_params == 0 || (reinterpret_cast<uintptr_t>(out) & 15u)) return RUDRA_EINVAL;
   for (uint32_t j = 0; j < k; ++j)
     if (!grads[j] || (reinterpret_cast<uintptr_t>(grads[j]) & 15u)) return RUDRA_EINVAL;
-  if (hipSetDevice(device) != hipSuccess) { (void)hipGetLastError(); return RUDRA_EHIP; }
+  DeviceGuard guard(device);
+  if (guard.error() != hipSuccess) { (void)hipGetLastError(); return RUDRA_EHIP; }
   const uint64_t n4 = n_params >> 2;
   const uint32_t block = kDefaultBlock;
   const uint64_t tiles = (n4 + block - 1) / block;
@@ -631,7 +660,8 @@ int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out) {
   if (dst) {
     if (ps->control_only) return RUDRA_ESTATE;
     if (ps->failed) return RUDRA_EHIP;
-    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    DeviceGuard guard(ps->cfg.device);
+    RUDRA_HIP(ps, guard.error());
     RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->theta2[ps->cur], ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
     ps->n_weight_copies += 1;
   } else {
@@ -657,7 +687,8 @@ int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst) {
   std::lock_guard<std::mutex> lock(ps->mu);
   if (ps->control_only) return RUDRA_ESTATE;
   if (ps->failed) return RUDRA_EHIP;
-  RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
   RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->vel, ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
   return RUDRA_OK;
 }
@@ -685,7 +716,8 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
   out->n_weight_views = ps->n_weight_views;
   if (ps->failed) return RUDRA_EHIP;
   if (ps->time_kernels) {
-    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    DeviceGuard guard(ps->cfg.device);
+    RUDRA_HIP(ps, guard.error());
     while (ps->timed_resolved < ps->timed_launches) {
       int rc = resolve_timer(ps, ps->timed_resolved);
       if (rc != RUDRA_OK) return rc;
@@ -694,7 +726,8 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
     out->kernel_launches = ps->timed_resolved;
   }
   if (ps->want_norms && ps->n_updates > 0 && ps->partials) {
-    RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+    DeviceGuard guard(ps->cfg.device);
+    RUDRA_HIP(ps, guard.error());
     std::vector<double> host((size_t)ps->last_apply_blocks * kNumNorms);
     RUDRA_HIP(ps, hipMemcpyAsync(host.data(), ps->partials, host.size() * sizeof(double), hipMemcpyDeviceToHost, ps->stream));
     RUDRA_HIP(ps, hipStreamSynchronize(ps->stream));
@@ -748,7 +781,8 @@ int rudra_ps_sync(rudra_ps_t* ps) {
   if (!ps) return RUDRA_EINVAL;
   std::lock_guard<std::mutex> lock(ps->mu);
   if (ps->control_only) return RUDRA_OK;
-  RUDRA_HIP(ps, hipSetDevice(ps->cfg.device));
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
   RUDRA_HIP(ps, hipStreamSynchronize(ps->stream));
   return RUDRA_OK;
 }
