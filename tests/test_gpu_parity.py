@@ -114,11 +114,13 @@ def test_c2_full_size_hardsync(hipmod):
 
 
 # ---------------------------------------------------------------- launch shapes, c from 1 past the fused limit, modes
-@pytest.mark.parametrize("block,unroll,vec,grid", [(64, 1, 1, 0), (256, 4, 1, 0), (256, 8, 1, 0), (512, 2, 2, 0),
-                                                    (1024, 2, 4, 0), (256, 4, 2, 3), (128, 1, 4, 7), (256, 2, 1, 1)])
-def test_launch_shapes_give_the_same_bits(hipmod, block, unroll, vec, grid):
+@pytest.mark.parametrize("block,unroll,vec,grid,waves,alternate", [
+    (64, 1, 1, 0, 0, 0), (256, 4, 1, 0, 32, 2), (256, 8, 1, 0, 4, 1), (512, 2, 2, 0, 0, 0), (1024, 2, 4, 0, 16, 0),
+    (256, 4, 2, 3, 0, 1), (128, 1, 4, 7, 2, 2), (256, 2, 1, 1, 0, 0), (64, 4, 2, 0, 8, 0)])
+def test_launch_shapes_give_the_same_bits(hipmod, block, unroll, vec, grid, waves, alternate):
     w = _with(configs.C4.scaled(n_params=33_331, n_pushes=18 * 4), weight_decay=5e-4)
-    hip, ora = _run_both(hipmod, w, launch_block=block, launch_unroll=unroll, launch_vec=vec, launch_grid=grid)
+    hip, ora = _run_both(hipmod, w, launch_block=block, launch_unroll=unroll, launch_vec=vec, launch_grid=grid,
+                         launch_waves_per_cu=waves, launch_alternate=alternate)
     _compare(hip, ora, w)
     hip.close()
 
