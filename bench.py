@@ -26,9 +26,9 @@ METRIC = "PS applyUpdates/sec and absorbed gradient GB/s (% HBM peak), 72M fp32 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
 
 # HBM bytes per applyUpdate launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE), each scaled by
-# the same counter's reading for a plain copy of known size (factors 1.99979 and 1.0); figures and commands in
+# the same counter's reading for a plain copy of known size (factors 1.99980 and 1.0); figures and commands in
 # profiles/apply_update_kernel_C4_C5_72M_hbm_traffic.md.  A measured constant, not recomputed at run time.
-MEASURED_TRAFFIC_BYTES = {"C4": 6.3354e9, "C5": 1.43994e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 6.3355e9, "C5": 1.43995e9}
 
 
 def algorithmic_bytes_per_update(w) -> int:
