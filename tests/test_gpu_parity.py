@@ -467,3 +467,24 @@ def test_tree_full_size_on_sampled_elements(hipmod):
     assert np.array_equal(hip.velocity()[sel].cpu().numpy(), ora.ps.velocity)
     assert hip.ps.stats().ts_cur == ora.ps.ts >= 19
     hip.close()
+
+
+def test_vectors_beyond_4_gib(hipmod):
+    """2^30 + 5 parameters: byte offsets pass 2^32 inside every stream, the tail is ragged, and the grid has 4.2M
+    workgroups.  Oracle on sampled positions around the 4 GiB boundary, the ends, and random ones."""
+    P = (1 << 30) + 5
+    w = _with(configs.C5.scaled(n_params=P, n_pushes=6), n_learners=3, n_split=1)        # c = 3, momentum + decay
+    around = np.arange((1 << 30) - 2048, P)                       # the last MiB-crossing tiles and the tail
+    idx = np.unique(np.concatenate([_sample_indices(P, 3, 4096), around])).astype(np.uint64)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w, ring=4), OracleServer(w, index=idx)
+    lh = replay.replay(hip, learner, step, w.n_learners)
+    lo = replay.replay(ora, learner, step, w.n_learners)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    sel = torch.from_numpy(idx.astype(np.int64)).cuda()
+    assert np.array_equal(hip.weights()[sel].cpu().numpy(), ora.ps.theta)
+    assert np.array_equal(hip.velocity()[sel].cpu().numpy(), ora.ps.velocity)
+    assert hip.ps.stats().ts_cur == 2
+    hip.close()
+    torch.cuda.empty_cache()
