@@ -488,3 +488,19 @@ def test_vectors_beyond_4_gib(hipmod):
     assert hip.ps.stats().ts_cur == 2
     hip.close()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("optimizer", ["sgd", "adagrad"])
+def test_subnormal_numbers_are_kept(hipmod, optimizer):
+    """Weights, gradients, steps and squared gradients in (and below) the subnormal range of binary32: the kernel must not
+    flush them to zero, the CPU does not."""
+    w = _with(configs.C3(2).scaled(n_params=20_001, n_pushes=150), init_std=3e-38, grad_std=2e-38 if optimizer == "sgd" else 1e-20,
+              alpha0=0.5, momentum=0.9 if optimizer == "sgd" else 0.0, weight_decay=0.25 if optimizer == "sgd" else 0.0, optimizer=optimizer, adagrad_eps=0.0 if optimizer == "sgd" else 1e-30)
+    hip, ora = _run_both(hipmod, w)
+    ref = ora.ps.theta
+    probe = ref if optimizer == "sgd" else ora.ps.velocity            # AdaGrad: the squared-gradient sums are the tiny ones
+    tiny = np.abs(probe[probe != 0]) < 1.1754944e-38
+    assert tiny.mean() > 0.2                          # the case really lives among subnormals
+    assert np.array_equal(hip.weights().cpu().numpy(), ref)
+    assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
+    hip.close()
