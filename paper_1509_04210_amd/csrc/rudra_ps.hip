@@ -421,20 +421,27 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   ps->c = gradients_per_update(*config);
   if (config->launch_block) ps->block = config->launch_block;
   if (config->launch_unroll) ps->unroll = config->launch_unroll;
+  else ps->unroll = ps->c > kDefaultUnroll ? 1u : kDefaultUnroll;  // many gradients: one load at a time per wave, more waves
   if (config->launch_vec) ps->vec = config->launch_vec;
   ps->grid_cap = config->launch_grid;
   ps->alternate = config->launch_alternate != 2;
   if (config->launch_waves_per_cu) {
     ps->waves_per_cu = config->launch_waves_per_cu;
   } else {
-    // about kInFlightKiBPerCu KiB of loads in flight per CU: each resident wave has theta, the second state vector
-    // and up to `unroll` gradient loads (1 KiB each) outstanding.  Waves that issue everything in one round
-    // (c <= unroll) spend a larger share of their life outside the load phase, so they get at least 12 slots
-    // (measured at 72M: c = 4 runs at 6.7-6.8 TB/s with 12 waves, 6.2-6.3 with 8).
+    // Measured at 72M parameters (GB/s of algorithmic bytes, medians): what counts is how many loads are in flight per
+    // CU, about kInFlightKiBPerCu KiB at 1 KiB per wave-load, and, at equal volume, that few tiles are open at once.
+    //   c <= 4: a wave issues theta, the second state vector and all its gradients in one round; 48/(loads per wave)
+    //           resident waves, at least 12 (c = 1: 16 waves 7.0 TB/s; c = 2: 12 waves 7.0; c = 4: 12 waves 6.7-6.8,
+    //           8 waves 6.2-6.3).
+    //   c > 4 with the default unroll of 1: after the first round a wave has one gradient load outstanding, and 26
+    //           resident waves are best (c = 7: 6.78, c = 18: 6.41, c = 30: 6.13, c = 54: 6.22; 20 or 32 waves lose
+    //           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind).
+    //   an explicit unroll > 1 with c above it: 48/(unroll + state vectors) waves.
     const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (kernel_optimizer(*config) != rudra::kOptSgd ? 1u : 0u);
     const uint32_t waves_per_wg = ps->block / 64;
     uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
     if (ps->c <= ps->unroll) w = std::max(w, 12u);
+    else if (ps->unroll == 1) w = 26;
     w = std::max(w, std::max(4u, waves_per_wg));
     ps->waves_per_cu = std::min(w, 32u);
   }
