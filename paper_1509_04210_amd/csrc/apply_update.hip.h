@@ -60,8 +60,11 @@ enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second 
 //               +9 % at c = 1).
 //   scope bits (sc0/sc1) make no difference (all 512 load/load/store policy combinations were tried).
 // Launch shape: one 64-lane wavefront per workgroup (6-8 % faster than 256-thread workgroups), and the host caps the
-// resident waves per CU (by reserving unused LDS) so that about 48 KiB of loads are in flight per CU: more
-// concurrent tiles keep more DRAM pages open at once and lose 3-6 %.
+// resident waves per CU by reserving unused LDS: what counts is the volume of loads in flight per CU and, at equal
+// volume, that few tiles are open at once (more concurrently open tiles keep more DRAM pages open and lose 3-6 %).
+// Measured optimum: c <= 4: all loads of a wave in one round, 12-16 waves; c > 4: ONE gradient load at a time per wave
+// (U = 1) and 26 waves.  Keeping 2-4 gradient loads rolling per wave, lanes that own 2-4 tiles (adjacent or strided),
+// per-XCD contiguous regions and grid-stride persistence were all measured and are slower or equal.
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
@@ -71,7 +74,7 @@ __device__ __forceinline__ void store_state4(floatx4* p, uint64_t iv, floatx4 x)
 
 // Sum of the c gradients at V vector positions, in arrival order.  Loads are issued U
 // gradients x V positions at a time before the first add that needs them, so each lane keeps
-// up to U*V independent 16-byte loads in flight.
+// up to U*V independent 16-byte loads in flight (the host picks U; see "Launch shape" above).
 template <bool WEIGHTED, int N, int V>
 __device__ __forceinline__ void add_n(const GradSet& gs, uint32_t j, const uint64_t (&iv)[V], floatx4 (&s)[V]) {
   floatx4 t[N][V];
