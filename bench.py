@@ -37,8 +37,10 @@ def algorithmic_bytes_per_update(w) -> int:
     return w.n_params * (4 * w.c + 8 + (8 if second_state else 0))
 
 
-def run_gpu(w, steps, warmup, ring=64, flags=0, **launch):
-    """Replays (warmup+steps)*c pushes of the workload's arrival trace; returns timings of the last `steps` updates."""
+def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, **launch):
+    """Replays (warmup+steps)*c pushes of the workload's arrival trace; returns timings of the last `steps` updates.
+    batch > 1: the messages are handed over `batch` at a time (rudra_ps_push_batch; a learner pulls after the call
+    that held its push), so consecutive updates share a launch."""
     import torch
     from paper_1509_04210_amd.learners import HipServer
 
@@ -64,10 +66,25 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, **launch):
             else:
                 learner_ts[l] = res.ts_after
 
+    def run_range_batched(lo, hi):
+        for i in range(lo, hi, batch):
+            m = min(batch, hi - i)
+            ls = learner[i:i + m]
+            rc, handled, res = ps.push_batch([bufs[(i + j) % nbuf] for j in range(m)], [learner_ts[l] for l in ls], ls)
+            if rc != 0 or handled != m:
+                raise RuntimeError(f"batch at push {i} rejected: {rc}")
+            now = res[-1].ts_after
+            for l in ls:
+                learner_ts[l] = now
+
+    if batch > 1:
+        assert not hard and nbuf >= batch + c
+        run_range = run_range_batched
     run_range(0, warmup * c)
     ps.sync()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    launches_before = 0 if flags & 8 else ps.stats().n_apply_launches     # (with the kernel timer on, stats() would wait)
     e0.record(hip.stream)
     t0 = time.perf_counter()
     run_range(warmup * c, (warmup + steps) * c)
@@ -79,7 +96,7 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, **launch):
     st = ps.stats()
     assert st.n_updates == warmup + steps, (st.n_updates, warmup + steps)
     out = dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * c, sigma_mean=st.sigma_mean,
-               kernel_ms=st.kernel_ms, kernel_launches=st.kernel_launches)
+               kernel_ms=st.kernel_ms, kernel_launches=st.kernel_launches, timed_launches=st.n_apply_launches - launches_before)
     # sanity: the state is finite and moved
     chk = hip.weights()
     out["theta_absmax"] = float(chk.abs().max())
@@ -181,6 +198,10 @@ def main():
     ap.add_argument("--vec", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
     ap.add_argument("--double-buffer", action="store_true", help="run the server with RUDRA_FLAG_DOUBLE_BUFFER")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="hand the messages over this many at a time (rudra_ps_push_batch): consecutive updates share a launch; "
+                         "the headline is measured with 1 (every update its own launch)")
+    ap.add_argument("--waves", type=int, default=0, help="launch_waves_per_cu")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
     ap.add_argument("--calibration-copies", type=int, default=0,
@@ -198,15 +219,18 @@ def main():
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid)
+    launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid,
+                  launch_waves_per_cu=args.waves)
     w = configs.ALL[args.workload]
     base_flags = B.FLAG_DOUBLE_BUFFER if args.double_buffer else 0
-    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, **launch)
+    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, batch=args.batch, **launch)
     bytes_upd = algorithmic_bytes_per_update(w)
+    if args.batch > 1:      # per launch: every gradient of its updates once, theta (and the second state vector) once
+        bytes_upd = (r["pushes"] * 4 * w.n_params + r["timed_launches"] * (bytes_upd - 4 * w.c * w.n_params)) // r["timed_launches"]
     ups = r["updates"] / r["wall_s"]
-    kernel_ms = r["event_ms"] / r["updates"]     # the timed region is back-to-back applyUpdate launches only
+    kernel_ms = r["event_ms"] / r["timed_launches"]     # the timed region is back-to-back applyUpdate launches only
     achieved = bytes_upd / (kernel_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else None
     line = {
         "metric": METRIC, "value": ups, "unit": "applyUpdates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * r["wall_s"] / r["updates"], "higher_is_better": True,
@@ -215,13 +239,13 @@ def main():
                                f"momentum={w.momentum}, wd={w.weight_decay}, lr=alpha0/max(1,<sigma>), "
                                f"ring of {max(args.ring, w.c + 1)} pre-generated gradients",
                    "pushes_per_step": w.c, "launch": {k: v for k, v in launch.items() if v},
-                   "double_buffer": bool(args.double_buffer)},
+                   "double_buffer": bool(args.double_buffer), "messages_per_call": args.batch},
         "absorbed_gradient_GBps": r["pushes"] * 4 * w.n_params / r["wall_s"] / 1e9,
         "pushes_per_s": r["pushes"] / r["wall_s"],
         "mean_staleness": r["sigma_mean"],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "apply_update_kernel", "bytes_per_launch": bytes_upd, "avg_launch_ms": kernel_ms},
+                     "kernel": "apply_update_kernel" if args.batch == 1 else "apply_update_batch_kernel", "bytes_per_launch": bytes_upd, "avg_launch_ms": kernel_ms},
     }
     if args.calibration_copies:
         src = torch.empty(w.n_params, dtype=torch.float32, device="cuda").normal_()

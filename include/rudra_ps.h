@@ -150,6 +150,8 @@ typedef struct {
   uint64_t n_ts_inquiries;  /* ... and those that only asked for the timestamp (Sec. 3.2 "Learner": a learner asks first
                                and skips the transfer when nothing changed) */
   uint64_t n_weight_views;  /* rudra_ps_weights_view calls */
+  uint64_t n_apply_launches;  /* applyUpdate kernel launches: equals n_updates unless rudra_ps_push_batch fused some */
+  uint64_t n_batched_updates; /* updates that shared a launch with at least one other update */
 } rudra_ps_stats_t;
 
 /* Create a server.  init_weights: DEVICE pointer to P floats (checked with the HIP runtime), copied (the caller keeps its buffer); in
@@ -175,6 +177,26 @@ int rudra_ps_destroy(rudra_ps_t* ps);
  * Errors: EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, EHIP. */
 int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out);
 
+/* A run of n pushGradient messages handled in one call: the gradients that queued up at the server while it was
+ * busy (Sec. 3.2: learners send with blocking calls and the server takes the messages one by one).  Message i is
+ * (grads[i], ts[i], learners[i]); the protocol state (staleness, vector clocks, rates, timestamps, statistics, rejections)
+ * is exactly what n calls of rudra_ps_push_gradient in this order would leave, and so are theta and v, bit for bit.
+ * What differs is the device work: consecutive updates completed inside the call are applied by ONE launch that
+ * keeps theta and v in registers from update to update (up to 64 updates / 64 gradients per launch), so u updates of c
+ * gradients move P*(4uc + 16) bytes instead of u*P*(4c + 16).  The weights of the timestamps in between are never
+ * stored: nothing can pull them, because no other call on this server runs inside this one.  This is the batching
+ * of per-gradient updates that small models and lambda-softsync (c = 1) need, where one launch per update is bound by
+ * launch latency or by re-reading theta and v.
+ *   grads    HOST array of n DEVICE pointers (each P floats, 16-byte aligned, borrowed as in rudra_ps_push_gradient;
+ *            safe to reuse after work enqueued on the stream after this call)
+ *   ts       HOST array of n timestamps;  learners: HOST array of n learner ids, or NULL (all anonymous)
+ *   out      HOST array of n results, or NULL;  n_handled: HOST pointer, or NULL
+ * The first rejected message stops the call: messages before it are handled (and their updates enqueued), it and
+ * the rest are not; its status is returned and *n_handled = its index (n when all were handled).
+ * With RUDRA_FLAG_PUSH_ACCUMULATE the call is the plain loop (the accumulator cannot be shared between updates). */
+int rudra_ps_push_batch(rudra_ps_t* ps, const float* const* grads, const uint64_t* ts, const int32_t* learners, uint32_t n,
+                        rudra_push_result_t* out, uint32_t* n_handled);
+
 /* The root of a parameter-server tree (Sec. 3.3) receiving what a node relays: avg = the average of m learner
  * gradients (see rudra_ps_leaf_mean), with the m timestamps of those gradients (HOST pointer ts) so that staleness,
  * vector clock and <sigma> stay exact.  It counts as m gradients: the running sum takes m*avg, applyUpdate fires once
@@ -198,8 +220,9 @@ int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out);
 /* Zero-copy pullWeights: a DEVICE pointer to the P weights of the current timestamp (HOST pointers theta_out, ts_out
  * receive it and the timestamp).  The weights are produced by work already enqueued on the server's stream: read them
  * on that stream, or after an event recorded on it.  With RUDRA_FLAG_DOUBLE_BUFFER the contents stay unchanged until the
- * SECOND update after this call is enqueued (the next update only reads this buffer); without it, only until the next
- * update is enqueued.  Read-only for the caller. */
+ * SECOND applyUpdate launch after this call is enqueued (the next launch only reads this buffer; a launch is one
+ * update, or the updates rudra_ps_push_batch fused); without it, only until the next update is enqueued.  Read-only
+ * for the caller. */
 int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_out);
 
 /* Copy of the momentum velocity v (DEVICE pointer to P floats), enqueued on the stream. */

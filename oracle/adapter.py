@@ -33,6 +33,17 @@ class OracleServer:
         rc, res = self.ps.push(self.w.grad_at(learner, step, self.index), ts, learner)
         return rc, int(res.staleness), int(res.applied)
 
+    def push_batch(self, messages):
+        """A run of messages: the oracle knows no batches, it takes them one by one."""
+        sigma, applied = [], []
+        for i, (l, s, ts) in enumerate(messages):
+            rc, sg, ap = self.push(l, s, ts)
+            if rc != 0:
+                return rc, i, sigma, applied
+            sigma.append(sg)
+            applied.append(ap)
+        return 0, len(messages), sigma, applied
+
     def push_aggregate(self, members, ts_list):
         """What a tree node relays for `members` = [(learner, step), ...]: their average, with their timestamps."""
         avg = leaf_mean([self.w.grad_at(l, s, self.index) for l, s in members], self.precision)

@@ -44,7 +44,7 @@ class Stats(C.Structure):
                 ("kernel_launches", C.c_uint64), ("pending", C.c_uint32), ("c", C.c_uint32),
                 ("last_lr", C.c_float), ("norms_valid", C.c_int32), ("last_hip_error", C.c_int32),
                 ("reserved", C.c_uint32), ("n_weight_copies", C.c_uint64), ("n_ts_inquiries", C.c_uint64),
-                ("n_weight_views", C.c_uint64)]
+                ("n_weight_views", C.c_uint64), ("n_apply_launches", C.c_uint64), ("n_batched_updates", C.c_uint64)]
 
 
 _lib = None
@@ -63,6 +63,8 @@ def lib():
             "rudra_ps_create": [C.POINTER(Config), vp, C.POINTER(vp)],
             "rudra_ps_destroy": [vp],
             "rudra_ps_push_gradient": [vp, vp, u64, i32, C.POINTER(PushResult)],
+            "rudra_ps_push_batch": [vp, C.POINTER(vp), C.POINTER(u64), C.POINTER(i32), u32, C.POINTER(PushResult),
+                                    C.POINTER(u32)],
             "rudra_ps_push_aggregate": [vp, vp, C.POINTER(u64), u32, C.POINTER(PushResult)],
             "rudra_ps_leaf_mean": [C.POINTER(vp), u32, u64, vp, i32, vp],
             "rudra_ps_pull_weights": [vp, vp, C.POINTER(u64)],
@@ -133,6 +135,17 @@ class ParameterServer:
         """(status, PushResult).  The PushResult object is reused by the next call."""
         rc = self._L.rudra_ps_push_gradient(self._h, grad_ptr or None, ts, learner, C.byref(self._res))
         return rc, self._res
+
+    def push_batch(self, grad_ptrs, ts_list, learners=None):
+        """rudra_ps_push_batch: a run of messages in one call.  (status, n_handled, [PushResult] * n_handled)."""
+        n = len(ts_list)
+        ptrs = (C.c_void_p * n)(*[p or None for p in grad_ptrs])
+        ts = (C.c_uint64 * n)(*ts_list)
+        ls = (C.c_int32 * n)(*learners) if learners is not None else None
+        res = (PushResult * n)()
+        handled = C.c_uint32()
+        rc = self._L.rudra_ps_push_batch(self._h, ptrs, ts, ls, n, res, C.byref(handled))
+        return rc, handled.value, res[:handled.value]
 
     def push_aggregate(self, avg_ptr, ts_list):
         """A relayed average standing for len(ts_list) learner gradients.  (status, PushResult)."""

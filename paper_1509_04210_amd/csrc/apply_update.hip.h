@@ -28,6 +28,7 @@ namespace rudra {
 
 constexpr int kMaxFused = 64;  // gradient pointers one launch can take (kernarg: 64*8 + 64*4 bytes)
 constexpr int kNumNorms = 4;   // gbar^2, theta^2, v^2, max|theta|
+constexpr int kMaxBatchUpdates = 64;  // consecutive updates one batched launch can apply
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -47,6 +48,15 @@ struct UpdateArgs {
   uint32_t c;        // gradients in this launch, 1..kMaxFused
   uint32_t reverse;  // 1: walk the tiles from the last to the first
   float inv_c, lr, momentum, weight_decay, adagrad_eps;
+};
+
+// The consecutive updates that one batched launch applies, in order: update u consumes the next count[u] gradients of
+// the GradSet (their counts sum to at most kMaxFused) with its own rate and its own 1/c.
+struct BatchPlan {
+  uint32_t n_updates;
+  uint8_t count[kMaxBatchUpdates];
+  float lr[kMaxBatchUpdates];
+  float inv_c[kMaxBatchUpdates];
 };
 
 enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second state vector, if any
@@ -256,6 +266,86 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       float s = sum_gradients_scalar<WEIGHTED>(gs, a.c, k);
       float th = a.theta[k], ve = (OPT != kOptSgd) ? a.vel[k] : 0.f;
       update_element<OPT, DECAY, STATS>(s, th, ve, a, n);
+      a.theta_out[k] = th;
+      if (OPT != kOptSgd) a.vel[k] = ve;
+    }
+  }
+  if (STATS) block_reduce_norms(n, a.partials);
+}
+
+// Several consecutive applyUpdates in one launch (a run of pushGradient messages that was handed over in one call):
+// theta and v are read once, carried in registers through the updates of the plan, and written once, so u updates
+// of c gradients move P*(4*u*c + 16) bytes instead of u*P*(4c + 16).  Every update is the same sequence of individually
+// rounded operations as in apply_update_kernel, applied in the same order, so the final state has the same bits; the
+// weights of the timestamps in between are never stored (nobody can ask for them inside one call).  One gradient
+// load is in flight per lane beyond the one being consumed: the first gradient of the next update is requested
+// before the arithmetic of the current one.  Norms (STATS) are those of the last update of the plan.
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
+__device__ __forceinline__ void batch_updates_vec4(const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a,
+                                                   uint64_t iv, floatx4& th, floatx4& ve, Norms& n) {
+  Norms unused = {0.f, 0.f, 0.f, 0.f};
+  UpdateArgs au = a;
+  floatx4 next = load_grad4(gs.p[0], iv);
+  uint32_t j = 0;
+  for (uint32_t u = 0; u < plan.n_updates; ++u) {
+    const uint32_t cnt = plan.count[u];
+    floatx4 s = next;
+    if (WEIGHTED) s = s * gs.w[j];
+    for (uint32_t l = 1; l < cnt; ++l) {
+      floatx4 t = load_grad4(gs.p[j + l], iv);
+      if (WEIGHTED) t = t * gs.w[j + l];
+      s = s + t;
+    }
+    j += cnt;
+    const bool last = u + 1 == plan.n_updates;
+    if (!last) next = load_grad4(gs.p[j], iv);
+    au.lr = plan.lr[u];
+    au.inv_c = plan.inv_c[u];
+    if (STATS && last) update_vec4<OPT, DECAY, true>(s, th, ve, au, n);
+    else update_vec4<OPT, DECAY, false>(s, th, ve, au, unused);
+  }
+}
+
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
+__global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan, const UpdateArgs a) {
+  const uint64_t n4 = a.n_params >> 2;
+  const uint64_t ntiles = a.ntiles;  // tiles of blockDim float4 positions
+  const floatx4* theta4 = reinterpret_cast<const floatx4*>(a.theta);
+  floatx4* theta_out4 = reinterpret_cast<floatx4*>(a.theta_out);
+  floatx4* vel4 = reinterpret_cast<floatx4*>(a.vel);
+  Norms n = {0.f, 0.f, 0.f, 0.f};
+  for (uint64_t t0 = blockIdx.x; t0 < ntiles; t0 += gridDim.x) {
+    const uint64_t t = a.reverse ? ntiles - 1 - t0 : t0;
+    const uint64_t iv = t * blockDim.x + threadIdx.x;
+    if (iv >= n4) continue;
+    floatx4 th = load_state4(theta4, iv), ve = {0.f, 0.f, 0.f, 0.f};
+    if (OPT != kOptSgd) ve = load_state4(vel4, iv);
+    batch_updates_vec4<OPT, DECAY, WEIGHTED, STATS>(gs, plan, a, iv, th, ve, n);
+    store_state4(theta_out4, iv, th);
+    if (OPT != kOptSgd) store_state4(vel4, iv, ve);
+  }
+  if (blockIdx.x == 0) {
+    const uint64_t k = (n4 << 2) + threadIdx.x;
+    if (k < a.n_params) {
+      float th = a.theta[k], ve = (OPT != kOptSgd) ? a.vel[k] : 0.f;
+      Norms unused = {0.f, 0.f, 0.f, 0.f};
+      UpdateArgs au = a;
+      uint32_t j = 0;
+      for (uint32_t u = 0; u < plan.n_updates; ++u) {
+        const uint32_t cnt = plan.count[u];
+        float s = load_grad1(gs.p[j], k);
+        if (WEIGHTED) s = s * gs.w[j];
+        for (uint32_t l = 1; l < cnt; ++l) {
+          float g = load_grad1(gs.p[j + l], k);
+          if (WEIGHTED) g = g * gs.w[j + l];
+          s = s + g;
+        }
+        j += cnt;
+        au.lr = plan.lr[u];
+        au.inv_c = plan.inv_c[u];
+        if (STATS && u + 1 == plan.n_updates) update_element<OPT, DECAY, true>(s, th, ve, au, n);
+        else update_element<OPT, DECAY, false>(s, th, ve, au, unused);
+      }
       a.theta_out[k] = th;
       if (OPT != kOptSgd) a.vel[k] = ve;
     }

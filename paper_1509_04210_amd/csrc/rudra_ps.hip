@@ -16,7 +16,9 @@
 
 #include "apply_update.hip.h"
 
+using rudra::BatchPlan;
 using rudra::GradSet;
+using rudra::kMaxBatchUpdates;
 using rudra::kMaxFused;
 using rudra::kNumNorms;
 using rudra::UpdateArgs;
@@ -29,6 +31,7 @@ constexpr uint32_t kDefaultVec = 1;
 constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding load bytes per compute unit
 constexpr uint32_t kDefaultClockRing = 1024;
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
+constexpr uint32_t kBatchWavesPerCu = 26;  // batched launches load one gradient at a time per wave, like c > 4
 
 // Makes `device` current for the calling thread and puts the previous one back on scope exit: a library call must
 // not leave the caller's thread on another device.
@@ -58,6 +61,13 @@ class DeviceGuard {
 struct Pending {
   const float* ptr;
   float weight;
+};
+
+struct DeferredUpdate {
+  uint32_t n_grads;  // entries of deferred_grads it consumes
+  uint32_t count;    // learner gradients it stands for (the divisor of the mean; > n_grads with relayed averages)
+  float lr;
+  bool weighted;
 };
 
 }  // namespace
@@ -108,6 +118,13 @@ struct rudra_ps {
   double last_avg = 0.0;
   float last_lr = 0.f;
   uint32_t last_apply_blocks = 0;
+  uint64_t n_apply_launches = 0;  // decides the direction of the next launch's walk over the vector
+  uint64_t n_batched_launches = 0, n_batched_updates = 0;
+
+  // rudra_ps_push_batch: updates that have fired but are not enqueued yet (flushed before the call returns)
+  bool deferring = false;
+  std::vector<Pending> deferred_grads;
+  std::vector<DeferredUpdate> deferred;
 
   // kernel timing
   std::vector<hipEvent_t> ev_start, ev_stop;
@@ -272,16 +289,40 @@ int resolve_timer(rudra_ps* ps, uint64_t launch_idx) {
   return RUDRA_OK;
 }
 
-// sumGradients + applyUpdate for the c pending gradients (Eq. 3 / Eq. 5), one fused launch
-// when c <= kMaxFused.
-int enqueue_update(rudra_ps* ps, float lr) {
-  const bool weighted = ps->open_weighted;
-  std::vector<Pending>& g = ps->open_grads;
+// HIP events around one applyUpdate launch (TIME_KERNELS): begin_timed before the launch, end_timed after it.
+int begin_timed(rudra_ps* ps, uint32_t* slot) {
+  *slot = 0;
+  if (!ps->time_kernels) return RUDRA_OK;
+  if (ps->timed_launches - ps->timed_resolved >= kTimerRing) {
+    int rc = resolve_timer(ps, ps->timed_resolved);
+    if (rc != RUDRA_OK) return rc;
+  }
+  *slot = (uint32_t)(ps->timed_launches % kTimerRing);
+  RUDRA_HIP(ps, hipEventRecord(ps->ev_start[*slot], ps->stream));
+  return RUDRA_OK;
+}
+int end_timed(rudra_ps* ps, uint32_t slot) {
+  if (!ps->time_kernels) return RUDRA_OK;
+  RUDRA_HIP(ps, hipEventRecord(ps->ev_stop[slot], ps->stream));
+  ps->timed_launches += 1;
+  return RUDRA_OK;
+}
+
+// Bookkeeping common to every applyUpdate launch: walk direction, double-buffer pointer swap.
+void after_apply_launch(rudra_ps* ps, uint32_t grid) {
+  ps->last_apply_blocks = grid;
+  ps->n_apply_launches += 1;
+  if (ps->double_buffer) ps->cur ^= 1u;  // the pointer swap: the buffer just written now holds the current weights
+}
+
+// sumGradients + applyUpdate for the `n` pending messages in `g` standing for `count` learner gradients (Eq. 3 /
+// Eq. 5), one fused launch when n <= kMaxFused.
+int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count, float lr, bool weighted) {
   size_t first = 0;
   Pending head = {nullptr, 1.0f};
   bool have_head = false;
   // fold leading groups into acc until what is left fits one launch
-  while ((g.size() - first) + (have_head ? 1 : 0) > (size_t)kMaxFused) {
+  while ((n_msgs - first) + (have_head ? 1 : 0) > (size_t)kMaxFused) {
     int rc = ensure_acc(ps);
     if (rc != RUDRA_OK) return rc;
     Pending group[kMaxFused];
@@ -297,34 +338,131 @@ int enqueue_update(rudra_ps* ps, float lr) {
   std::memset(&gs, 0, sizeof(gs));
   uint32_t n = 0;
   if (have_head) { gs.p[n] = head.ptr; gs.w[n] = head.weight; ++n; }
-  for (; first < g.size(); ++first, ++n) { gs.p[n] = g[first].ptr; gs.w[n] = g[first].weight; }
+  for (; first < n_msgs; ++first, ++n) { gs.p[n] = g[first].ptr; gs.w[n] = g[first].weight; }
 
   UpdateArgs a = base_args(ps);
   a.c = n;
-  a.inv_c = 1.0f / (float)ps->count;  // Eq. 5: the mean is over all gradients of the update (c of them, unless a
-                                      // relayed average made the count overshoot)
+  a.inv_c = 1.0f / (float)count;  // Eq. 5: the mean is over all gradients of the update (c of them, unless a
+                                  // relayed average made the count overshoot)
   a.lr = lr;
-  a.reverse = (ps->alternate && (ps->n_updates & 1)) ? 1u : 0u;
+  a.reverse = (ps->alternate && (ps->n_apply_launches & 1)) ? 1u : 0u;
   const LaunchShape s = shape_for(ps);
   a.ntiles = s.ntiles;
   uint32_t slot = 0;
-  if (ps->time_kernels) {
-    if (ps->timed_launches - ps->timed_resolved >= kTimerRing) {
-      int rc = resolve_timer(ps, ps->timed_resolved);
-      if (rc != RUDRA_OK) return rc;
-    }
-    slot = (uint32_t)(ps->timed_launches % kTimerRing);
-    RUDRA_HIP(ps, hipEventRecord(ps->ev_start[slot], ps->stream));
-  }
+  int rc = begin_timed(ps, &slot);
+  if (rc != RUDRA_OK) return rc;
   launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
   RUDRA_HIP(ps, hipGetLastError());
-  if (ps->time_kernels) {
-    RUDRA_HIP(ps, hipEventRecord(ps->ev_stop[slot], ps->stream));
-    ps->timed_launches += 1;
-  }
-  ps->last_apply_blocks = s.grid;
-  if (ps->double_buffer) ps->cur ^= 1u;  // the pointer swap: the buffer just written now holds the current weights
+  rc = end_timed(ps, slot);
+  if (rc != RUDRA_OK) return rc;
+  after_apply_launch(ps, s.grid);
   return RUDRA_OK;
+}
+
+// ---- batched launches: several consecutive updates applied in registers (rudra_ps_push_batch) ----
+template <int OPT, bool WD>
+void launch_batch_ws(bool weighted, bool stats, LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan,
+                     const UpdateArgs& a) {
+  if (weighted) {
+    if (stats) hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, true, true>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+    else hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, true, false>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  } else {
+    if (stats) hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, false, true>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+    else hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, false, false>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  }
+}
+void launch_batch(int opt, bool decay, bool weighted, bool stats, LaunchShape s, hipStream_t st, const GradSet& gs,
+                  const BatchPlan& plan, const UpdateArgs& a) {
+  switch (opt) {
+    case rudra::kOptMomentum:
+      if (decay) launch_batch_ws<rudra::kOptMomentum, true>(weighted, stats, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptMomentum, false>(weighted, stats, s, st, gs, plan, a);
+      break;
+    case rudra::kOptAdagrad:
+      if (decay) launch_batch_ws<rudra::kOptAdagrad, true>(weighted, stats, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptAdagrad, false>(weighted, stats, s, st, gs, plan, a);
+      break;
+    default:
+      if (decay) launch_batch_ws<rudra::kOptSgd, true>(weighted, stats, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptSgd, false>(weighted, stats, s, st, gs, plan, a);
+      break;
+  }
+}
+
+// Launch shape of a batched launch: one float4 per lane per tile whatever launch_vec says (theta and v stay in
+// registers across the updates of the plan).
+LaunchShape batch_shape_for(const rudra_ps* ps) {
+  const uint64_t n4 = ps->cfg.n_params >> 2;
+  const uint64_t tiles = (n4 + ps->block - 1) / ps->block;
+  uint64_t grid = tiles ? tiles : 1;
+  if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
+  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
+  const uint32_t waves = ps->cfg.launch_waves_per_cu ? ps->cfg.launch_waves_per_cu : std::max(kBatchWavesPerCu, ps->block / 64);
+  return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(waves, ps->block)};
+}
+
+// Enqueue the updates `d[0..n_upd)` (consuming consecutive entries of `g`) as ONE batched launch.  Caller guarantees
+// 2 <= n_upd <= kMaxBatchUpdates, every update <= 255 messages, and at most kMaxFused messages in total.
+int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint32_t n_upd) {
+  GradSet gs;
+  BatchPlan plan;
+  std::memset(&gs, 0, sizeof(gs));
+  std::memset(&plan, 0, sizeof(plan));
+  uint32_t n = 0;
+  bool weighted = false;
+  plan.n_updates = n_upd;
+  for (uint32_t u = 0; u < n_upd; ++u) {
+    plan.count[u] = (uint8_t)d[u].n_grads;
+    plan.lr[u] = d[u].lr;
+    plan.inv_c[u] = 1.0f / (float)d[u].count;
+    weighted = weighted || d[u].weighted;
+    for (uint32_t j = 0; j < d[u].n_grads; ++j, ++n) { gs.p[n] = g[n].ptr; gs.w[n] = g[n].weight; }
+  }
+  UpdateArgs a = base_args(ps);
+  a.c = n;
+  a.reverse = (ps->alternate && (ps->n_apply_launches & 1)) ? 1u : 0u;
+  const LaunchShape s = batch_shape_for(ps);
+  a.ntiles = s.ntiles;
+  uint32_t slot = 0;
+  int rc = begin_timed(ps, &slot);
+  if (rc != RUDRA_OK) return rc;
+  launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, s, ps->stream, gs, plan, a);
+  RUDRA_HIP(ps, hipGetLastError());
+  rc = end_timed(ps, slot);
+  if (rc != RUDRA_OK) return rc;
+  after_apply_launch(ps, s.grid);
+  ps->n_batched_launches += 1;
+  ps->n_batched_updates += n_upd;
+  return RUDRA_OK;
+}
+
+// Enqueue everything rudra_ps_push_batch has deferred: runs of consecutive updates that fit one launch go out as
+// one batched launch, a lone update (or one too large to batch) through the single-update path.
+int flush_deferred(rudra_ps* ps) {
+  const std::vector<DeferredUpdate>& d = ps->deferred;
+  const Pending* g = ps->deferred_grads.data();
+  size_t i = 0, g0 = 0;
+  int rc = RUDRA_OK;
+  while (i < d.size() && rc == RUDRA_OK) {
+    size_t k = i, msgs = 0;
+    while (k < d.size() && k - i < (size_t)kMaxBatchUpdates && d[k].n_grads <= (uint32_t)kMaxFused &&
+           msgs + d[k].n_grads <= (size_t)kMaxFused) {
+      msgs += d[k].n_grads;
+      ++k;
+    }
+    if (k - i >= 2) {
+      rc = enqueue_batch(ps, g + g0, &d[i], (uint32_t)(k - i));
+      g0 += msgs;
+      i = k;
+    } else {
+      rc = enqueue_update(ps, g + g0, d[i].n_grads, d[i].count, d[i].lr, d[i].weighted);
+      g0 += d[i].n_grads;
+      i += 1;
+    }
+  }
+  ps->deferred.clear();
+  ps->deferred_grads.clear();
+  return rc;
 }
 
 // true if [p, p + bytes) is device memory of `device` according to the HIP runtime
@@ -475,7 +613,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
     if (e == hipSuccess) e = hipMemcpyAsync(ps->theta2[0], init_weights, bytes, hipMemcpyDeviceToDevice, ps->stream);
     if (e == hipSuccess) e = hipMemsetAsync(ps->vel, 0, bytes, ps->stream);
     if (e == hipSuccess && ps->want_norms) {
-      ps->partials_blocks = shape_for(ps).grid;
+      ps->partials_blocks = std::max(shape_for(ps).grid, batch_shape_for(ps).grid);
       e = hipMalloc((void**)&ps->partials, (size_t)ps->partials_blocks * kNumNorms * sizeof(double));
     }
     if (e == hipSuccess && ps->time_kernels) {
@@ -541,8 +679,13 @@ static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t 
         ps->open_grads.clear();
         ps->open_grads.push_back({ps->acc, 1.0f});
       }
-      int rc = enqueue_update(ps, lr_used);
-      if (rc != RUDRA_OK) { ps->failed = true; return rc; }
+      if (ps->deferring) {  // rudra_ps_push_batch enqueues it, fused with its neighbours, before it returns
+        ps->deferred_grads.insert(ps->deferred_grads.end(), ps->open_grads.begin(), ps->open_grads.end());
+        ps->deferred.push_back({(uint32_t)ps->open_grads.size(), ps->count, lr_used, ps->open_weighted});
+      } else {
+        int rc = enqueue_update(ps, ps->open_grads.data(), ps->open_grads.size(), ps->count, lr_used, ps->open_weighted);
+        if (rc != RUDRA_OK) { ps->failed = true; return rc; }
+      }
     }
     const size_t slot = (size_t)(ps->n_updates % ps->ring);
     std::copy(ps->open_clock.begin(), ps->open_clock.begin() + ps->count, ps->ring_ts.begin() + slot * ps->clock_cap);
@@ -580,14 +723,10 @@ static int check_pushed_pointer(rudra_ps* ps, const float* grad) {
   return RUDRA_OK;
 }
 
-int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
-  if (!ps) return RUDRA_EINVAL;
-  std::lock_guard<std::mutex> lock(ps->mu);
-  if (ps->failed) return RUDRA_EHIP;
+// One pushGradient message: validation (a rejected message changes nothing but the rejection counter), then absorb.
+// Caller holds the mutex and has made the device current.
+static int push_one(rudra_ps* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
   const rudra_ps_config_t& cfg = ps->cfg;
-  DeviceGuard guard(ps->control_only ? -1 : cfg.device);
-  if (guard.error() != hipSuccess) return hip_fail(ps, guard.error());
-  // ---- validation: a rejected message changes nothing but the rejection counter ----
   int rc = check_pushed_pointer(ps, grad);
   if (rc == RUDRA_EHIP) return rc;
   if (rc != RUDRA_OK) { ps->n_rejected++; return rc; }
@@ -604,6 +743,45 @@ int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32
     ps->open_weighted = true;  // every update of this mode runs the weighted kernel
   }
   return absorb(ps, grad, &ts, 1, learner, weight, out);
+}
+
+int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->failed) return RUDRA_EHIP;
+  DeviceGuard guard(ps->control_only ? -1 : ps->cfg.device);
+  if (guard.error() != hipSuccess) return hip_fail(ps, guard.error());
+  return push_one(ps, grad, ts, learner, out);
+}
+
+int rudra_ps_push_batch(rudra_ps_t* ps, const float* const* grads, const uint64_t* ts, const int32_t* learners, uint32_t n,
+                        rudra_push_result_t* out, uint32_t* n_handled) {
+  if (n_handled) *n_handled = 0;
+  if (!ps || (n && !ts) || (n && !grads && !(ps->cfg.flags & RUDRA_FLAG_CONTROL_ONLY))) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->failed) return RUDRA_EHIP;
+  DeviceGuard guard(ps->control_only ? -1 : ps->cfg.device);
+  if (guard.error() != hipSuccess) return hip_fail(ps, guard.error());
+  // accumulate-at-push reuses one accumulator from update to update, so its updates cannot wait for each other
+  ps->deferring = !ps->control_only && !ps->accumulate;
+  int rc = RUDRA_OK;
+  uint32_t i = 0;
+  try {
+    for (; i < n; ++i) {
+      rc = push_one(ps, grads ? grads[i] : nullptr, ts[i], learners ? learners[i] : -1, out ? out + i : nullptr);
+      if (rc != RUDRA_OK) break;  // the messages before it stay handled; this one and the rest are not
+    }
+  } catch (const std::bad_alloc&) {
+    rc = RUDRA_ENOMEM;
+    ps->failed = true;  // the protocol state is ahead of the device state: nothing more can be trusted
+  }
+  ps->deferring = false;
+  if (n_handled) *n_handled = i;
+  if (!ps->failed) {
+    const int frc = flush_deferred(ps);
+    if (frc != RUDRA_OK) { ps->failed = true; return frc; }
+  }
+  return rc;
 }
 
 int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts, uint32_t m, rudra_push_result_t* out) {
@@ -721,6 +899,8 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
   out->n_weight_copies = ps->n_weight_copies;
   out->n_ts_inquiries = ps->n_ts_inquiries;
   out->n_weight_views = ps->n_weight_views;
+  out->n_apply_launches = ps->n_apply_launches;
+  out->n_batched_updates = ps->n_batched_updates;
   if (ps->failed) return RUDRA_EHIP;
   if (ps->time_kernels) {
     DeviceGuard guard(ps->cfg.device);

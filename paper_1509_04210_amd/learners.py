@@ -67,6 +67,20 @@ class HipServer:
         rc, res = self.ps.push_gradient(buf.data_ptr(), ts, learner)
         return rc, res.staleness, res.applied
 
+    def push_batch(self, messages):
+        """rudra_ps_push_batch for `messages` = [(learner, step, ts), ...]: every gradient is materialised into its own
+        ring buffer first (the ring must hold the batch plus whatever was pending before it)."""
+        assert len(messages) + self.w.c <= len(self.ring) or self.pregenerated, "ring too small for this batch"
+        ptrs = []
+        for l, s, _ in messages:
+            buf = self.ring[self._next]
+            self._next = (self._next + 1) % (self.pregenerated or len(self.ring))
+            if not self.pregenerated:
+                self._fill(buf, l, s)
+            ptrs.append(buf.data_ptr())
+        rc, handled, res = self.ps.push_batch(ptrs, [ts for _, _, ts in messages], [l for l, _, _ in messages])
+        return rc, handled, [r.staleness for r in res], [r.applied for r in res]
+
     def push_aggregate(self, members, ts_list):
         """A tree node's work for `members` = [(learner, step), ...]: materialise their gradients, average them on the
         device (rudra_ps_leaf_mean) and relay the average with the members' timestamps to the root."""

@@ -72,3 +72,36 @@ def replay_tree(server, learner, step, n_learners, fan_in, hardsync=False):
     out = {k: np.array(v, dtype=np.int64) for k, v in log.items()}
     out["left_in_nodes"] = sum(len(n) for n in waiting)
     return out
+
+
+def replay_batched(server, learner, step, n_learners, chunk_sizes, hardsync=False, c=1):
+    """The same learners when the server takes the messages that have queued up in one call: the trace is cut into
+    chunks of the given sizes (cycled), and each chunk is one
+        push_batch(messages) -> (rc, n_handled, staleness list, applied list)     # messages: [(learner, step, ts), ...]
+    A learner stamps its gradient with the timestamp of its last pull and pulls again only after the chunk that held
+    its push was handled (a learner appearing twice in a chunk sends both gradients with the same stamp).  Under
+    hardsync the stamp must equal the server's timestamp at arrival, which is the number of completed rounds.
+    Returns the same log as replay(), minus ts_at_arrival."""
+    n = len(learner)
+    learner_ts = np.zeros(n_learners, dtype=np.int64)
+    log = dict(ts_pushed=np.zeros(n, np.int64), staleness=np.zeros(n, np.int64), applied=np.zeros(n, np.int64))
+    i, k = 0, 0
+    while i < n:
+        m = min(int(chunk_sizes[k % len(chunk_sizes)]), n - i)
+        k += 1
+        msgs = []
+        for j in range(i, i + m):
+            l = int(learner[j])
+            ts = j // c if hardsync else int(learner_ts[l])
+            msgs.append((l, int(step[j]), ts))
+            log["ts_pushed"][j] = ts
+        rc, handled, sigma, applied = server.push_batch(msgs)
+        if rc != 0 or handled != m:
+            raise RuntimeError(f"batch at push {i} stopped after {handled} of {m} messages: {rc}")
+        log["staleness"][i:i + m] = sigma
+        log["applied"][i:i + m] = applied
+        now = server.pull_ts()
+        for l, _, _ in msgs:
+            learner_ts[l] = now
+        i += m
+    return log

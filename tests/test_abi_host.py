@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in include/rudra_ps.h but not exported"
-    assert len(declared) == 14
+    assert len(declared) == 15
 
 
 def test_struct_layouts_match_the_header():
@@ -98,6 +98,10 @@ class _Control:
         rc, r = self.ps.push_gradient(0, ts, l)
         return rc, r.staleness, r.applied
 
+    def push_batch(self, msgs):
+        rc, handled, res = self.ps.push_batch([0] * len(msgs), [ts for _, _, ts in msgs], [l for l, _, _ in msgs])
+        return rc, handled, [r.staleness for r in res], [r.applied for r in res]
+
     def pull_ts(self):
         return self.ps.pull_weights(0)
 
@@ -116,8 +120,58 @@ class _OracleControl:
         rc, r = self.ps.push(self.g, ts, l)
         return rc, int(r.staleness), int(r.applied)
 
+    def push_batch(self, msgs):
+        out = [self.push(l, s, ts) for l, s, ts in msgs]
+        return 0, len(msgs), [o[1] for o in out], [o[2] for o in out]
+
     def pull_ts(self):
         return self.ps.ts
+
+
+def _same_protocol_state(hip, ora):
+    st, o = hip.ps.stats(), ora.ps
+    assert (st.ts_cur, st.n_pushes, st.n_updates, st.pending, st.c) == (o.ts, o.n_pushes, o.n_updates, o.pending, o.c)
+    assert (st.sigma_sum, st.sigma_max, st.n_rejected) == (o.sigma_sum, o.sigma_max, o.n_rejected)
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), o.hist)
+    clocks, avg, lr = o.clocks, o.avg_staleness, o.lr_log
+    for u in range(o.n_updates):
+        ts, a, r = hip.ps.vector_clock(u)
+        assert ts == list(clocks[u]) and a == avg[u] and np.float32(r) == lr[u]
+
+
+@pytest.mark.parametrize("name", list(configs.ALL))
+def test_batched_pushes_leave_the_protocol_state_of_single_pushes(name):
+    """rudra_ps_push_batch == the same messages through the oracle one by one (control plane; chunks of 1..40)."""
+    w = configs.ALL[name]
+    n = min(w.n_pushes, 3000)
+    learner, step = w.arrival_trace(n)
+    chunks = np.random.default_rng(11).integers(1, 41, size=64)
+    hard = w.protocol == "hardsync"
+    hip, ora = _Control(w, clock_ring=8192), _OracleControl(w)
+    lh = replay.replay_batched(hip, learner, step, w.n_learners, chunks, hardsync=hard, c=w.c)
+    lo = replay.replay_batched(ora, learner, step, w.n_learners, chunks, hardsync=hard, c=w.c)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    _same_protocol_state(hip, ora)
+
+
+def test_a_rejected_message_stops_the_batch_where_single_pushes_would_reject_it():
+    ps = R.ParameterServer(4, 3, n_split=3, lr_mode=B.LR_CONST, alpha0=0.5, flags=B.FLAG_CONTROL_ONLY)      # c = 1
+    ora = OraclePS(np.zeros(4, np.float32), 3, 3, oracle.SOFTSYNC, oracle.LR_CONST, alpha0=0.5)
+    g = np.zeros(4, np.float32)
+    ts, learners = [0, 1, 1, 9, 2, 0], [0, 1, 2, 0, 1, 7]            # message 3 comes from the future
+    rc, handled, res = ps.push_batch([0] * 6, ts, learners)
+    assert (rc, handled, len(res)) == (B.EFUTURE_TS, 3, 3)
+    want = [ora.push(g, t, l) for t, l in zip(ts[:4], learners[:4])]
+    assert [w[0] for w in want] == [0, 0, 0, oracle.EFUTURE_TS]
+    for r, (_, ro) in zip(res, want):
+        assert (r.staleness, r.ts_after, r.pending, r.applied, r.lr_used) == (ro.staleness, ro.ts_after, ro.pending, ro.applied, ro.lr_used)
+    st = ps.stats()
+    assert (st.ts_cur, st.n_pushes, st.n_rejected) == (3, 3, 1) == (ora.ts, ora.n_pushes, ora.n_rejected)
+    rc, handled, res = ps.push_batch([0] * 2, ts[4:], learners[4:])    # the rest: message 5 names an unknown learner
+    assert (rc, handled) == (B.EINVAL, 1) and ps.stats().ts_cur == 4
+    assert ps.push_batch([], [], [])[:2] == (B.OK, 0)
+    assert R.lib().rudra_ps_push_batch(None, None, None, None, 0, None, None) == B.EINVAL
 
 
 @pytest.mark.parametrize("name", list(configs.ALL))

@@ -504,3 +504,101 @@ def test_subnormal_numbers_are_kept(hipmod, optimizer):
     assert np.array_equal(hip.weights().cpu().numpy(), ref)
     assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
     hip.close()
+
+
+# ---------------------------------------------------------------- rudra_ps_push_batch: consecutive updates fused into one launch
+def _run_both_batched(learners, w, chunks, flags=0, ring=None, **launch):
+    learner, step = w.arrival_trace()
+    hard = w.protocol == "hardsync"
+    hip = learners.HipServer(w, flags=flags, ring=ring or (max(chunks) + w.c + 1), **launch)
+    ora = OracleServer(w)
+    lh = replay.replay_batched(hip, learner, step, w.n_learners, chunks, hardsync=hard, c=w.c)
+    lo = replay.replay_batched(ora, learner, step, w.n_learners, chunks, hardsync=hard, c=w.c)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    return hip, ora
+
+
+BATCH_CASES = {
+    # name: (workload, chunk sizes cycled over the trace)
+    "c1-momentum-decay": (configs.C5.scaled(n_params=40_003, n_pushes=400), [1, 2, 3, 7, 16, 64, 65, 100, 5]),
+    "c1-sgd": (_with(configs.C3(30).scaled(n_params=9_999, n_pushes=300)), [64, 1, 63, 2, 128]),
+    "c4-no-momentum": (configs.C1.scaled(n_params=131_072, n_pushes=256), [9, 4, 1, 31, 8]),
+    "c7-stragglers": (configs.C3(4).scaled(n_params=20_001, n_pushes=500), [50, 3, 14, 70]),
+    "c18-heavy-tail": (configs.C4.scaled(n_params=33_331, n_pushes=18 * 12), [40, 18, 5, 72]),
+    "hardsync-c30": (configs.C2.scaled(n_params=10_007, n_pushes=30 * 9), [45, 30, 7, 90]),
+    "adagrad": (_with(configs.C4_ADAGRAD.scaled(n_params=5_555, n_pushes=18 * 10), n_learners=6, weight_decay=5e-4), [13, 2, 30]),
+    "per-gradient-weights": (_with(configs.C3(10).scaled(n_params=7_777, n_pushes=400), lr_mode="per_gradient", momentum=0.9), [25, 6, 64]),
+    "c70-beyond-one-launch": (_with(configs.C3(1).scaled(n_params=4_099, n_pushes=70 * 4 + 3), n_learners=70, c_override=70, momentum=0.9), [150, 9]),
+    "c33-two-updates-do-not-fit": (_with(configs.C3(1).scaled(n_params=4_099, n_pushes=33 * 7), n_learners=33, c_override=33), [100, 33, 98]),
+    "tiny-vectors": (configs.C5.scaled(n_params=3, n_pushes=50), [8, 5]),
+}
+
+
+@pytest.mark.parametrize("name", list(BATCH_CASES))
+def test_batched_pushes_give_the_bits_of_single_pushes(hipmod, name):
+    """Messages handed over in runs (rudra_ps_push_batch) against the oracle, which takes them one by one: same
+    staleness / applied per message, same clocks and rates, same theta and v to the bit."""
+    w, chunks = BATCH_CASES[name]
+    hip, ora = _run_both_batched(hipmod, w, chunks)
+    _compare(hip, ora, w)
+    st = hip.ps.stats()
+    assert st.n_apply_launches <= st.n_updates
+    if w.c <= 32 and max(chunks) >= 2 * w.c:
+        assert st.n_batched_updates > 0 and st.n_apply_launches < st.n_updates     # something was fused
+    hip.close()
+
+
+@pytest.mark.parametrize("P", [1, 4, 5, 63, 64, 65, 257, 1024 + 3])
+def test_batched_pushes_on_ragged_vectors(hipmod, P):
+    w = configs.C5.scaled(n_params=P, n_pushes=40)
+    hip, ora = _run_both_batched(hipmod, w, [6, 11, 2])
+    _compare(hip, ora, w)
+    hip.close()
+
+
+@pytest.mark.parametrize("block,grid,waves,alternate", [(64, 0, 0, 0), (256, 3, 4, 1), (1024, 0, 32, 2), (128, 1, 0, 0)])
+def test_batched_launch_shapes_give_the_same_bits(hipmod, block, grid, waves, alternate):
+    w = configs.C5.scaled(n_params=50_001, n_pushes=120)
+    hip, ora = _run_both_batched(hipmod, w, [10, 33], launch_block=block, launch_grid=grid, launch_waves_per_cu=waves,
+                                 launch_alternate=alternate, launch_vec=2)
+    _compare(hip, ora, w)
+    hip.close()
+
+
+def test_batched_pushes_with_norms_timer_double_buffer_and_accumulate(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = configs.C5.scaled(n_params=77_777, n_pushes=90)
+    hip, ora = _run_both_batched(hipmod, w, [7, 20], flags=B.FLAG_STATS_NORMS | B.FLAG_TIME_KERNELS | B.FLAG_DOUBLE_BUFFER)
+    _compare(hip, ora, w)
+    st, ref = hip.ps.stats(), ora.ps.norms()
+    assert st.norms_valid == 1 and st.kernel_launches == st.n_apply_launches < st.n_updates
+    for got, want in [(st.theta_sq, ref["theta_sq"]), (st.v_sq, ref["v_sq"]), (st.gbar_sq, ref["gbar_sq"])]:
+        assert abs(got - want) <= 1e-5 * want                  # norms are those of the last update of the last launch
+    assert st.theta_inf == ref["theta_inf"]
+    hip.close()
+    hip, ora = _run_both_batched(hipmod, w, [7, 20], flags=B.FLAG_PUSH_ACCUMULATE)     # the plain loop: nothing is fused
+    _compare(hip, ora, w)
+    assert hip.ps.stats().n_apply_launches == hip.ps.stats().n_updates
+    hip.close()
+
+
+def test_batched_c5_full_size_on_sampled_elements(hipmod):
+    """The lambda-softsync workload at 72M parameters, 5000 pushes handed over 16 at a time (16 updates per launch)."""
+    w = configs.C5
+    idx = _sample_indices(w.n_params, 9, 16384)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w, ring=16 + w.c + 1), OracleServer(w, index=idx)
+    lh = replay.replay_batched(hip, learner, step, w.n_learners, [16])
+    lo = replay.replay_batched(ora, learner, step, w.n_learners, [16])
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    sel = torch.from_numpy(idx.astype(np.int64)).cuda()
+    th, ve = hip.weights()[sel].cpu().numpy(), hip.velocity()[sel].cpu().numpy()
+    assert np.abs(th.astype(np.float64) - ora.ps.theta).max() <= TOL * np.abs(ora.ps.theta).max()
+    assert np.array_equal(th, ora.ps.theta) and np.array_equal(ve, ora.ps.velocity)
+    st = hip.ps.stats()
+    assert (st.ts_cur, st.n_pushes, st.sigma_sum, st.sigma_max) == (ora.ps.ts, 5000, ora.ps.sigma_sum, ora.ps.sigma_max)
+    assert st.n_apply_launches == -(-5000 // 16)
+    assert bool(torch.isfinite(hip.weights()).all())
+    hip.close()
