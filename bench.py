@@ -70,7 +70,9 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, **launch):
         for i in range(lo, hi, batch):
             m = min(batch, hi - i)
             ls = learner[i:i + m]
-            rc, handled, res = ps.push_batch([bufs[(i + j) % nbuf] for j in range(m)], [learner_ts[l] for l in ls], ls)
+            # hardsync: a gradient must carry the timestamp current at its arrival = the number of completed rounds
+            ts = [(i + j) // c for j in range(m)] if hard else [learner_ts[l] for l in ls]
+            rc, handled, res = ps.push_batch([bufs[(i + j) % nbuf] for j in range(m)], ts, ls)
             if rc != 0 or handled != m:
                 raise RuntimeError(f"batch at push {i} rejected: {rc}")
             now = res[-1].ts_after
@@ -78,7 +80,7 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, **launch):
                 learner_ts[l] = now
 
     if batch > 1:
-        assert not hard and nbuf >= batch + c
+        assert nbuf >= batch + c
         run_range = run_range_batched
     run_range(0, warmup * c)
     ps.sync()
@@ -273,6 +275,17 @@ def main():
                 "avg_launch_ms": o_ms, "achieved_GBps": bo / (o_ms * 1e-3) / 1e9,
                 "frac": bo / (o_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "bytes_per_launch": bo,
                 "mean_staleness": ro["sigma_mean"]}
+    if not args.no_extra and args.batch == 1:
+        # C5 again with the messages handed over 8 at a time (rudra_ps_push_batch): 8 updates per launch, theta and v
+        # touched once per launch: P*(4*8 + 16) bytes instead of 8*P*20
+        rb = run_gpu(configs.C5, 1024, 64, ring=max(args.ring, 64), flags=base_flags, batch=8, **launch)
+        bb = (rb["pushes"] * 4 + rb["timed_launches"] * 16) * configs.C5.n_params // rb["timed_launches"]
+        b_ms = rb["event_ms"] / rb["timed_launches"]
+        line["extra"]["C5-8-messages-per-call"] = {
+            "applyUpdates_per_s": rb["updates"] / rb["wall_s"], "absorbed_gradient_GBps": rb["pushes"] * 4 * configs.C5.n_params / rb["wall_s"] / 1e9,
+            "avg_launch_ms": b_ms, "updates_per_launch": rb["updates"] / rb["timed_launches"], "bytes_per_launch": bb,
+            "achieved_GBps": bb / (b_ms * 1e-3) / 1e9, "frac": bb / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "kernel": "apply_update_batch_kernel"}
     if not args.no_extra:
         # 54 learners, 1-softsync (the shape of the paper's Rudra-adv ImageNet run, Table 4): flat, and as a tree with nodes of 3
         from dataclasses import replace

@@ -277,36 +277,53 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 // theta and v are read once, carried in registers through the updates of the plan, and written once, so u updates
 // of c gradients move P*(4*u*c + 16) bytes instead of u*P*(4c + 16).  Every update is the same sequence of individually
 // rounded operations as in apply_update_kernel, applied in the same order, so the final state has the same bits; the
-// weights of the timestamps in between are never stored (nobody can ask for them inside one call).  One gradient
-// load is in flight per lane beyond the one being consumed: the first gradient of the next update is requested
-// before the arithmetic of the current one.  Norms (STATS) are those of the last update of the plan.
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
+// weights of the timestamps in between are never stored (nobody can ask for them inside one call).  D gradient
+// loads are kept in flight per lane across update boundaries.  Norms (STATS) are those of the last update of the plan.
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int D>
 __device__ __forceinline__ void batch_updates_vec4(const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a,
                                                    uint64_t iv, floatx4& th, floatx4& ve, Norms& n) {
+  // The gradients of all updates form one list gs.p[0 .. a.c); D of them are kept in flight per lane (slot d holds
+  // gradient j0 + d and is refilled with gradient j0 + d + D as soon as it has been taken), while a small state machine
+  // (pos, cnt, u: all wave-uniform) walks the plan and applies an update whenever its last gradient has been added.
+  const uint32_t total = a.c;
   Norms unused = {0.f, 0.f, 0.f, 0.f};
   UpdateArgs au = a;
-  floatx4 next = load_grad4(gs.p[0], iv);
-  uint32_t j = 0;
-  for (uint32_t u = 0; u < plan.n_updates; ++u) {
-    const uint32_t cnt = plan.count[u];
-    floatx4 s = next;
-    if (WEIGHTED) s = s * gs.w[j];
-    for (uint32_t l = 1; l < cnt; ++l) {
-      floatx4 t = load_grad4(gs.p[j + l], iv);
-      if (WEIGHTED) t = t * gs.w[j + l];
-      s = s + t;
+  floatx4 q[D];
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if ((uint32_t)d < total) q[d] = load_grad4(gs.p[d], iv);
+  uint32_t u = 0, pos = 0, cnt = plan.count[0];
+  au.lr = plan.lr[0];
+  au.inv_c = plan.inv_c[0];
+  floatx4 s = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t j0 = 0; j0 < total; j0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const uint32_t j = j0 + d;
+      if (j < total) {
+        floatx4 g = q[d];
+        if (j + D < total) q[d] = load_grad4(gs.p[j + D], iv);
+        if (WEIGHTED) g = g * gs.w[j];
+        if (pos == 0) s = g;
+        else s = s + g;
+        if (++pos == cnt) {
+          const bool last = u + 1 == plan.n_updates;
+          if (STATS && last) update_vec4<OPT, DECAY, true>(s, th, ve, au, n);
+          else update_vec4<OPT, DECAY, false>(s, th, ve, au, unused);
+          pos = 0;
+          if (!last) {
+            ++u;
+            cnt = plan.count[u];
+            au.lr = plan.lr[u];
+            au.inv_c = plan.inv_c[u];
+          }
+        }
+      }
     }
-    j += cnt;
-    const bool last = u + 1 == plan.n_updates;
-    if (!last) next = load_grad4(gs.p[j], iv);
-    au.lr = plan.lr[u];
-    au.inv_c = plan.inv_c[u];
-    if (STATS && last) update_vec4<OPT, DECAY, true>(s, th, ve, au, n);
-    else update_vec4<OPT, DECAY, false>(s, th, ve, au, unused);
   }
 }
 
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int D>
 __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t ntiles = a.ntiles;  // tiles of blockDim float4 positions
@@ -320,7 +337,7 @@ __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan
     if (iv >= n4) continue;
     floatx4 th = load_state4(theta4, iv), ve = {0.f, 0.f, 0.f, 0.f};
     if (OPT != kOptSgd) ve = load_state4(vel4, iv);
-    batch_updates_vec4<OPT, DECAY, WEIGHTED, STATS>(gs, plan, a, iv, th, ve, n);
+    batch_updates_vec4<OPT, DECAY, WEIGHTED, STATS, D>(gs, plan, a, iv, th, ve, n);
     store_state4(theta_out4, iv, th);
     if (OPT != kOptSgd) store_state4(vel4, iv, ve);
   }
