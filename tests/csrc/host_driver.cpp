@@ -73,6 +73,27 @@ int main() {
   for (auto& x : th) x.join();
   CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK);
   CHECK(st.n_pushes == 300 + 18000 && st.n_updates == 100 + 6000);
+  // runs of messages in one call, from several threads; a run that holds a message from the future stops there
+  {
+    std::vector<uint64_t> stamps(50, 0);
+    std::vector<int32_t> who(50);
+    for (int i = 0; i < 50; ++i) who[i] = i % 7;
+    std::vector<rudra_push_result_t> res(50);
+    uint32_t handled = 0;
+    CHECK(rudra_ps_push_batch(ps, nullptr, stamps.data(), who.data(), 50, res.data(), &handled) == RUDRA_OK && handled == 50);
+    CHECK(res[49].ts_after == 6100 + 16 && res[49].pending == 2);
+    stamps[20] = ~0ull;
+    CHECK(rudra_ps_push_batch(ps, nullptr, stamps.data(), nullptr, 50, nullptr, &handled) == RUDRA_EFUTURE_TS && handled == 20);
+    CHECK(rudra_ps_push_batch(ps, nullptr, nullptr, nullptr, 0, nullptr, nullptr) == RUDRA_OK);
+    CHECK(rudra_ps_push_batch(ps, nullptr, nullptr, nullptr, 3, nullptr, nullptr) == RUDRA_EINVAL);
+    stamps[20] = 0;
+    std::vector<std::thread> tb;
+    for (int t = 0; t < 4; ++t)
+      tb.emplace_back([ps, &stamps] { for (int i = 0; i < 200; ++i) rudra_ps_push_batch(ps, nullptr, stamps.data(), nullptr, 50, nullptr, nullptr); });
+    for (auto& x : tb) x.join();
+    CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK);
+    CHECK(st.n_pushes == 18300 + 50 + 20 + 4 * 200 * 50 && st.n_rejected == 3 + 1);
+  }
   CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
   // hardsync: duplicates and stale gradients
   cfg.protocol = RUDRA_HARDSYNC;

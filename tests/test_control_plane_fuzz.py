@@ -34,7 +34,23 @@ def test_random_message_sequences(lam, data):
         # timestamps around the current one (past, present, future), learners around the valid range
         ts = max(0, ora.ts + data.draw(st.integers(-4, 1)))
         learner = data.draw(st.integers(-2, lam))
-        if data.draw(st.integers(0, 3)) == 0:      # a relayed average of 1..max+1 gradients (one too many is rejected)
+        kind = data.draw(st.integers(0, 4))
+        if kind == 4:                              # a run of messages in one call: stops at the first one the oracle rejects
+            msgs = [(max(0, ora.ts + data.draw(st.integers(-4, 2))), data.draw(st.integers(-1, lam))) for _ in range(data.draw(st.integers(0, 7)))]
+            rc_h, handled, res = ps.push_batch([0] * len(msgs), [m[0] for m in msgs], [m[1] for m in msgs])
+            rc_o, k = 0, 0
+            for ts_m, l_m in msgs:
+                rc_o, ro = ora.push(g, ts_m, l_m)
+                if rc_o != 0:
+                    break
+                r = res[k]
+                assert (r.staleness, r.ts_after, r.pending, r.applied, np.float32(r.lr_used)) == \
+                       (ro.staleness, ro.ts_after, ro.pending, ro.applied, np.float32(ro.lr_used))
+                k += 1
+            assert (rc_h, handled) == (rc_o, k)
+            assert ps.pull_weights(0) == ora.ts
+            continue
+        if kind == 0:      # a relayed average of 1..max+1 gradients (one too many is rejected)
             stamps = [max(0, ora.ts + data.draw(st.integers(-3, 1))) for _ in range(data.draw(st.integers(1, max(1, max_agg) + 1)))]
             rc_h, r = ps.push_aggregate(0, stamps)
             rc_o, ro = ora.push_aggregate(g, stamps)

