@@ -29,6 +29,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
 # the same counter's reading for a plain copy of known size (factors 1.99980 and 1.0); figures and commands in
 # profiles/apply_update_kernel_C4_C5_72M_hbm_traffic.md.  A measured constant, not recomputed at run time.
 MEASURED_TRAFFIC_BYTES = {"C4": 6.3355e9, "C5": 1.43995e9}
+MEASURED_TRAFFIC_BYTES_BATCH8 = {"C5": 3.4558e9}   # same files: C5 with 8 messages per call
 
 
 def algorithmic_bytes_per_update(w) -> int:
@@ -152,6 +153,27 @@ def run_gpu_tree(w, fan_in, steps, warmup, ring=64):
     return dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * w.c)
 
 
+def run_copy_ceiling(n_params, reps=20):
+    """What a plain device-to-device copy of one parameter vector reaches on this machine (read + write bytes over time):
+    context for the roofline fraction, not a target."""
+    import torch
+    src = torch.empty(n_params, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del src, dst
+    torch.cuda.empty_cache()
+    return 8 * n_params / (ms * 1e-3) / 1e9
+
+
 def run_cpu_oracle(w, n_updates=30, n_distinct=3):
     """The CPU oracle as it stands, single thread, on the full-size vector: `n_updates` applyUpdates of the same
     workload.  Gradient materialisation is excluded from the timing (as on the GPU)."""
@@ -232,7 +254,8 @@ def main():
     ups = r["updates"] / r["wall_s"]
     kernel_ms = r["event_ms"] / r["timed_launches"]     # the timed region is back-to-back applyUpdate launches only
     achieved = bytes_upd / (kernel_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else None
+    traffic = (MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else
+               MEASURED_TRAFFIC_BYTES_BATCH8.get(args.workload) if args.batch == 8 else None)
     line = {
         "metric": METRIC, "value": ups, "unit": "applyUpdates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * r["wall_s"] / r["updates"], "higher_is_better": True,
@@ -257,6 +280,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_extra:
+        line["roofline"]["device_copy_GBps"] = run_copy_ceiling(w.n_params)
         # per-launch HIP events around every applyUpdate (library flag), same workload
         rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=base_flags | B.FLAG_TIME_KERNELS, **launch)
         k_ms = rt["kernel_ms"] / max(1, rt["kernel_launches"])
