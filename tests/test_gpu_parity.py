@@ -611,3 +611,16 @@ def test_batched_c5_full_size_on_sampled_elements(hipmod):
     assert st.n_apply_launches == -(-5000 // 16)
     assert bool(torch.isfinite(hip.weights()).all())
     hip.close()
+
+
+# ---------------------------------------------------------------- the C ABI from a plain C++ program, against closed forms
+def test_c_abi_from_a_plain_program_matches_closed_forms(hipmod):
+    """tests/csrc/abi_gpu_check.cpp: hipMalloc'ed constant vectors pushed through the C ABI (single pushes, a batched
+    run, a tree node + root), every result compared with a closed form that binary32 holds exactly.  Neither torch
+    nor the oracle is involved: a pin of the HIP path that is independent of both."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "abi_gpu_check")
+    assert os.path.exists(exe), f"{exe} is missing: run __graft_entry__.build()"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0 and "abi gpu check ok" in r.stdout, r.stdout + r.stderr
