@@ -53,10 +53,14 @@ struct UpdateArgs {
 // The consecutive updates that one batched launch applies, in order: update u consumes the next count[u] gradients of
 // the GradSet (their counts sum to at most kMaxFused) with its own rate and its own 1/c.
 struct BatchPlan {
+  struct Entry {     // 16 bytes: one scalar load fetches a whole entry
+    uint32_t count;  // gradients of this update
+    float lr, inv_c;
+    uint32_t pad;
+  };
   uint32_t n_updates;
-  uint8_t count[kMaxBatchUpdates];
-  float lr[kMaxBatchUpdates];
-  float inv_c[kMaxBatchUpdates];
+  uint32_t pad[3];
+  Entry e[kMaxBatchUpdates];
 };
 
 enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second state vector, if any
@@ -77,6 +81,11 @@ enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second 
 // per-XCD contiguous regions and grid-stride persistence were all measured and are slower or equal.
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
+}
+// the same load from an address held as an integer (global address space stated explicitly)
+__device__ __forceinline__ floatx4 load_grad4_global(uint64_t p, uint64_t iv) {
+  typedef const __attribute__((address_space(1))) floatx4* global_floatx4_ptr;
+  return __builtin_nontemporal_load(reinterpret_cast<global_floatx4_ptr>(p) + iv);
 }
 __device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
 __device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return p[iv]; }
@@ -110,6 +119,32 @@ __device__ __forceinline__ void sum_gradients(const GradSet& gs, uint32_t c, con
     if (WEIGHTED) s[v] = s[v] * gs.w[0];
   }
   uint32_t j = 1;
+  if (U == 1) {
+    // One gradient at a time: the pointer (and weight) of the next gradient is fetched from the kernarg while the
+    // current gradient is in flight, so the scalar load's latency is off the wave's load-wait-add chain.
+    uint64_t p_cur = reinterpret_cast<uint64_t>(gs.p[1]);
+    float w_cur = gs.w[1];
+    for (; j < c; ++j) {
+      floatx4 t[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) t[v] = load_grad4_global(p_cur, iv[v]);
+      const uint32_t jn = j + 1 < (uint32_t)kMaxFused ? j + 1 : j;
+      uint64_t p_next = reinterpret_cast<uint64_t>(gs.p[jn]);
+      float w_next = gs.w[jn];
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        if (WEIGHTED) t[v] = t[v] * w_cur;
+        s[v] = s[v] + t[v];
+      }
+      // the next pointer has to be in its registers here, after the wait for the gradient: without this the
+      // compiler moves the scalar load to the top of the next iteration, back in front of the vector load
+      if (WEIGHTED) asm volatile("" : "+s"(p_next), "+s"(w_next));
+      else asm volatile("" : "+s"(p_next));
+      p_cur = p_next;
+      w_cur = w_next;
+    }
+    return;
+  }
   for (; j + U <= c; j += U) add_n<WEIGHTED, U, V>(gs, j, iv, s);
   if (U > 4 && (c - j) & 4u) { add_n<WEIGHTED, 4, V>(gs, j, iv, s); j += 4; }
   if (U > 2 && (c - j) & 2u) { add_n<WEIGHTED, 2, V>(gs, j, iv, s); j += 2; }
@@ -277,92 +312,100 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 // theta and v are read once, carried in registers through the updates of the plan, and written once, so u updates
 // of c gradients move P*(4*u*c + 16) bytes instead of u*P*(4c + 16).  Every update is the same sequence of individually
 // rounded operations as in apply_update_kernel, applied in the same order, so the final state has the same bits; the
-// weights of the timestamps in between are never stored (nobody can ask for them inside one call).  D gradient
-// loads are kept in flight per lane across update boundaries.  Norms (STATS) are those of the last update of the plan.
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int D>
-__device__ __forceinline__ void batch_updates_vec4(const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a,
-                                                   uint64_t iv, floatx4& th, floatx4& ve, Norms& n) {
-  // The gradients of all updates form one list gs.p[0 .. a.c); D of them are kept in flight per lane (slot d holds
-  // gradient j0 + d and is refilled with gradient j0 + d + D as soon as it has been taken), while a small state machine
-  // (pos, cnt, u: all wave-uniform) walks the plan and applies an update whenever its last gradient has been added.
+// weights of the timestamps in between are never stored (nobody can ask for them inside one call).  Norms (STATS)
+// are those of the last update of the plan.
+//
+// A lane owns one position of type T: a float4, or, for the P % 4 tail done by workgroup 0, a single float.
+template <typename T>
+__device__ __forceinline__ T load_grad_global(uint64_t p, uint64_t i) {  // non-temporal, global address space stated
+  typedef const __attribute__((address_space(1))) T* global_ptr;
+  return __builtin_nontemporal_load(reinterpret_cast<global_ptr>(p) + i);
+}
+template <int OPT, bool DECAY, bool STATS>
+__device__ __forceinline__ void update_lane(const floatx4& s, floatx4& th, floatx4& ve, const UpdateArgs& a, Norms& n) {
+  update_vec4<OPT, DECAY, STATS>(s, th, ve, a, n);
+}
+template <int OPT, bool DECAY, bool STATS>
+__device__ __forceinline__ void update_lane(const float& s, float& th, float& ve, const UpdateArgs& a, Norms& n) {
+  update_element<OPT, DECAY, STATS>(s, th, ve, a, n);
+}
+
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, typename T>
+__device__ __forceinline__ void batch_updates(const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a, uint64_t i,
+                                              T& th, T& ve, Norms& n) {
+  // The gradients of all updates form one list gs.p[0 .. a.c).  Gradient j is consumed (added and, if it completes an
+  // update, that update applied) while the load of gradient j+1 is in flight; right behind that load the pointer (and
+  // weight) of gradient j+2 and the plan entry of the next update are fetched from the kernarg.  pos, u, the pointers
+  // and the plan entries are wave-uniform (scalar registers).  The empty asm pins the prefetched scalars into their
+  // registers there: without it the compiler moves the scalar loads down to their first use, i.e. in front of the
+  // next vector load, where their latency adds to the wave's load-wait-compute chain.  The last gradient is
+  // consumed after the loop, so every iteration issues exactly one load and the wait counts stay exact.
   const uint32_t total = a.c;
   Norms unused = {0.f, 0.f, 0.f, 0.f};
   UpdateArgs au = a;
-  floatx4 q[D];
-#pragma unroll
-  for (int d = 0; d < D; ++d)
-    if ((uint32_t)d < total) q[d] = load_grad4(gs.p[d], iv);
-  uint32_t u = 0, pos = 0, cnt = plan.count[0];
-  au.lr = plan.lr[0];
-  au.inv_c = plan.inv_c[0];
-  floatx4 s = {0.f, 0.f, 0.f, 0.f};
-  for (uint32_t j0 = 0; j0 < total; j0 += D) {
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-      const uint32_t j = j0 + d;
-      if (j < total) {
-        floatx4 g = q[d];
-        if (j + D < total) q[d] = load_grad4(gs.p[j + D], iv);
-        if (WEIGHTED) g = g * gs.w[j];
-        if (pos == 0) s = g;
-        else s = s + g;
-        if (++pos == cnt) {
-          const bool last = u + 1 == plan.n_updates;
-          if (STATS && last) update_vec4<OPT, DECAY, true>(s, th, ve, au, n);
-          else update_vec4<OPT, DECAY, false>(s, th, ve, au, unused);
-          pos = 0;
-          if (!last) {
-            ++u;
-            cnt = plan.count[u];
-            au.lr = plan.lr[u];
-            au.inv_c = plan.inv_c[u];
-          }
-        }
-      }
+  uint32_t u = 0, pos = 0;
+  BatchPlan::Entry cur = plan.e[0], nxt = plan.e[1];
+  T s{};
+  // gradient g with weight w joins the running sum; if it is the last one of update u, that update is applied
+  auto consume = [&](T g, float w) {
+    if (WEIGHTED) g = g * w;
+    if (pos == 0) s = g;
+    else s = s + g;
+    if (++pos == cur.count) {
+      au.lr = cur.lr;
+      au.inv_c = cur.inv_c;
+      if (STATS && u + 1 == plan.n_updates) update_lane<OPT, DECAY, true>(s, th, ve, au, n);
+      else update_lane<OPT, DECAY, false>(s, th, ve, au, unused);
+      pos = 0;
+      ++u;
+      cur = nxt;
     }
+  };
+  T g = load_grad_global<T>(reinterpret_cast<uint64_t>(gs.p[0]), i);
+  uint64_t p_next = reinterpret_cast<uint64_t>(gs.p[1]);
+  float w_cur = gs.w[0], w_next = gs.w[1];
+  for (uint32_t j = 0; j + 1 < total; ++j) {  // gradient j is consumed while gradient j+1 is in flight
+    T g_next = load_grad_global<T>(p_next, i);
+    const uint32_t jn = j + 2 < (uint32_t)kMaxFused ? j + 2 : (uint32_t)kMaxFused - 1;
+    const uint32_t un = u + 1 < (uint32_t)kMaxBatchUpdates ? u + 1 : u;
+    uint64_t p_after = reinterpret_cast<uint64_t>(gs.p[jn]);
+    float w_after = gs.w[jn];
+    nxt = plan.e[un];
+    if (WEIGHTED) asm volatile("" : "+s"(p_after), "+s"(w_after), "+s"(nxt.count), "+s"(nxt.lr), "+s"(nxt.inv_c));
+    else asm volatile("" : "+s"(p_after), "+s"(nxt.count), "+s"(nxt.lr), "+s"(nxt.inv_c));
+    consume(g, w_cur);
+    g = g_next;
+    p_next = p_after;
+    w_cur = w_next;
+    w_next = w_after;
   }
+  consume(g, w_cur);
 }
 
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int D>
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
 __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan, const UpdateArgs a) {
-  const uint64_t n4 = a.n_params >> 2;
-  const uint64_t ntiles = a.ntiles;  // tiles of blockDim float4 positions
-  const floatx4* theta4 = reinterpret_cast<const floatx4*>(a.theta);
-  floatx4* theta_out4 = reinterpret_cast<floatx4*>(a.theta_out);
-  floatx4* vel4 = reinterpret_cast<floatx4*>(a.vel);
+  typedef floatx4 T;
+  const uint64_t npos = a.n_params >> 2;
+  const uint64_t ntiles = a.ntiles;  // tiles of blockDim positions
+  const T* theta = reinterpret_cast<const T*>(a.theta);  // may alias theta_out: each position is read, then
+  T* theta_out = reinterpret_cast<T*>(a.theta_out);      // written, by one lane
+  T* vel = reinterpret_cast<T*>(a.vel);
   Norms n = {0.f, 0.f, 0.f, 0.f};
   for (uint64_t t0 = blockIdx.x; t0 < ntiles; t0 += gridDim.x) {
     const uint64_t t = a.reverse ? ntiles - 1 - t0 : t0;
-    const uint64_t iv = t * blockDim.x + threadIdx.x;
-    if (iv >= n4) continue;
-    floatx4 th = load_state4(theta4, iv), ve = {0.f, 0.f, 0.f, 0.f};
-    if (OPT != kOptSgd) ve = load_state4(vel4, iv);
-    batch_updates_vec4<OPT, DECAY, WEIGHTED, STATS, D>(gs, plan, a, iv, th, ve, n);
-    store_state4(theta_out4, iv, th);
-    if (OPT != kOptSgd) store_state4(vel4, iv, ve);
+    const uint64_t i = t * blockDim.x + threadIdx.x;
+    if (i >= npos) continue;
+    T th = theta[i], ve{};
+    if (OPT != kOptSgd) ve = vel[i];
+    batch_updates<OPT, DECAY, WEIGHTED, STATS, T>(gs, plan, a, i, th, ve, n);
+    __builtin_nontemporal_store(th, theta_out + i);
+    if (OPT != kOptSgd) __builtin_nontemporal_store(ve, vel + i);
   }
-  if (blockIdx.x == 0) {
-    const uint64_t k = (n4 << 2) + threadIdx.x;
+  if (blockIdx.x == 0) {  // the P % 4 elements behind the last float4
+    const uint64_t k = (npos << 2) + threadIdx.x;
     if (k < a.n_params) {
       float th = a.theta[k], ve = (OPT != kOptSgd) ? a.vel[k] : 0.f;
-      Norms unused = {0.f, 0.f, 0.f, 0.f};
-      UpdateArgs au = a;
-      uint32_t j = 0;
-      for (uint32_t u = 0; u < plan.n_updates; ++u) {
-        const uint32_t cnt = plan.count[u];
-        float s = load_grad1(gs.p[j], k);
-        if (WEIGHTED) s = s * gs.w[j];
-        for (uint32_t l = 1; l < cnt; ++l) {
-          float g = load_grad1(gs.p[j + l], k);
-          if (WEIGHTED) g = g * gs.w[j + l];
-          s = s + g;
-        }
-        j += cnt;
-        au.lr = plan.lr[u];
-        au.inv_c = plan.inv_c[u];
-        if (STATS && u + 1 == plan.n_updates) update_element<OPT, DECAY, true>(s, th, ve, au, n);
-        else update_element<OPT, DECAY, false>(s, th, ve, au, unused);
-      }
+      batch_updates<OPT, DECAY, WEIGHTED, STATS, float>(gs, plan, a, k, th, ve, n);
       a.theta_out[k] = th;
       if (OPT != kOptSgd) a.vel[k] = ve;
     }

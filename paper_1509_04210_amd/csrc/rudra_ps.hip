@@ -31,12 +31,10 @@ constexpr uint32_t kDefaultVec = 1;
 constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding load bytes per compute unit
 constexpr uint32_t kDefaultClockRing = 1024;
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
-// Batched launches (measured at 72M parameters, c = 1, 8 / 16 / 64 messages per launch): 2 gradient loads in flight per
-// lane (1: -1 %, 4: -3 to -15 %); every step down in resident waves costs bandwidth (8 waves: -40 %), because between two
-// loads a wave does a whole update's arithmetic and fetches the next pointer and rate; 26 waves up to 16 messages
-// (6.6 / 6.2 TB/s), all 32 beyond (5.8 TB/s at 64).
-constexpr int kBatchDepth = 2;
-constexpr uint32_t kBatchWavesPerCu = 26, kBatchWavesPerCuLong = 32, kBatchLongFrom = 17;
+// Batched launches (measured at 72M parameters, c = 1, 4 to 64 messages per launch, and at 1.0M and 131k parameters):
+// 26 resident waves are best or equal everywhere (16: -3 to -12 %, 32: -1 to -3 %): between two loads a wave does a
+// whole update's arithmetic, so it takes more waves than the single-update kernel to keep the memory system busy.
+constexpr uint32_t kBatchWavesPerCu = 26;
 
 // Makes `device` current for the calling thread and puts the previous one back on scope exit: a library call must
 // not leave the caller's thread on another device.
@@ -367,7 +365,7 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
 // ---- batched launches: several consecutive updates applied in registers (rudra_ps_push_batch) ----
 template <int OPT, bool WD, bool W, bool ST>
 void launch_batch_d(LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
-  hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, kBatchDepth>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
 }
 template <int OPT, bool WD>
 void launch_batch_ws(bool weighted, bool stats, LaunchShape s, hipStream_t st, const GradSet& gs,
@@ -400,19 +398,18 @@ void launch_batch(int opt, bool decay, bool weighted, bool stats, LaunchShape s,
 
 // Launch shape of a batched launch: one float4 per lane per tile whatever launch_vec says (theta and v stay in
 // registers across the updates of the plan).
-LaunchShape batch_shape_for(const rudra_ps* ps, uint32_t n_msgs = 0) {
-  const uint64_t n4 = ps->cfg.n_params >> 2;
-  const uint64_t tiles = (n4 + ps->block - 1) / ps->block;
+LaunchShape batch_shape_for(const rudra_ps* ps) {
+  const uint64_t npos = ps->cfg.n_params >> 2;
+  const uint64_t tiles = (npos + ps->block - 1) / ps->block;
   uint64_t grid = tiles ? tiles : 1;
   if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
   if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
-  const uint32_t dflt = n_msgs >= kBatchLongFrom ? kBatchWavesPerCuLong : kBatchWavesPerCu;
-  const uint32_t waves = ps->cfg.launch_waves_per_cu ? ps->cfg.launch_waves_per_cu : std::max(dflt, ps->block / 64);
+  const uint32_t waves = ps->cfg.launch_waves_per_cu ? ps->cfg.launch_waves_per_cu : std::max(kBatchWavesPerCu, ps->block / 64);
   return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(waves, ps->block)};
 }
 
 // Enqueue the updates `d[0..n_upd)` (consuming consecutive entries of `g`) as ONE batched launch.  Caller guarantees
-// 2 <= n_upd <= kMaxBatchUpdates, every update <= 255 messages, and at most kMaxFused messages in total.
+// 2 <= n_upd <= kMaxBatchUpdates and at most kMaxFused messages in total.
 int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint32_t n_upd) {
   GradSet gs;
   BatchPlan plan;
@@ -422,16 +419,16 @@ int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint3
   bool weighted = false;
   plan.n_updates = n_upd;
   for (uint32_t u = 0; u < n_upd; ++u) {
-    plan.count[u] = (uint8_t)d[u].n_grads;
-    plan.lr[u] = d[u].lr;
-    plan.inv_c[u] = 1.0f / (float)d[u].count;
+    plan.e[u].count = d[u].n_grads;
+    plan.e[u].lr = d[u].lr;
+    plan.e[u].inv_c = 1.0f / (float)d[u].count;
     weighted = weighted || d[u].weighted;
     for (uint32_t j = 0; j < d[u].n_grads; ++j, ++n) { gs.p[n] = g[n].ptr; gs.w[n] = g[n].weight; }
   }
   UpdateArgs a = base_args(ps);
   a.c = n;
   a.reverse = (ps->alternate && (ps->n_apply_launches & 1)) ? 1u : 0u;
-  const LaunchShape s = batch_shape_for(ps, n);
+  const LaunchShape s = batch_shape_for(ps);
   a.ntiles = s.ntiles;
   uint32_t slot = 0;
   int rc = begin_timed(ps, &slot);

@@ -541,6 +541,12 @@ BATCH_CASES = {
     "c70-beyond-one-launch": (_with(configs.C3(1).scaled(n_params=4_099, n_pushes=70 * 4 + 3), n_learners=70, c_override=70, momentum=0.9), [150, 9]),
     "c33-two-updates-do-not-fit": (_with(configs.C3(1).scaled(n_params=4_099, n_pushes=33 * 7), n_learners=33, c_override=33), [100, 33, 98]),
     "tiny-vectors": (configs.C5.scaled(n_params=3, n_pushes=50), [8, 5]),
+    # larger vectors (thousands of tiles), ragged tails
+    "wide-c1-momentum-decay": (configs.C5.scaled(n_params=600_003, n_pushes=150), [1, 2, 3, 7, 16, 64, 65]),
+    "wide-c18-heavy-tail": (configs.C4.scaled(n_params=524_288 + 2, n_pushes=18 * 8), [40, 18, 5, 72]),
+    "wide-adagrad": (_with(configs.C4_ADAGRAD.scaled(n_params=555_555, n_pushes=6 * 10), n_learners=6, weight_decay=5e-4), [13, 2, 30]),
+    "wide-per-gradient-weights": (_with(configs.C3(10).scaled(n_params=524_289, n_pushes=200), lr_mode="per_gradient", momentum=0.9), [25, 6, 64]),
+    "wide-hardsync-c30": (configs.C2.scaled(n_pushes=30 * 6), [45, 30, 7, 90]),
 }
 
 
@@ -568,24 +574,26 @@ def test_batched_pushes_on_ragged_vectors(hipmod, P):
 
 @pytest.mark.parametrize("block,grid,waves,alternate", [(64, 0, 0, 0), (256, 3, 4, 1), (1024, 0, 32, 2), (128, 1, 0, 0)])
 def test_batched_launch_shapes_give_the_same_bits(hipmod, block, grid, waves, alternate):
-    w = configs.C5.scaled(n_params=50_001, n_pushes=120)
-    hip, ora = _run_both_batched(hipmod, w, [10, 33], launch_block=block, launch_grid=grid, launch_waves_per_cu=waves,
-                                 launch_alternate=alternate, launch_vec=2)
-    _compare(hip, ora, w)
-    hip.close()
+    for P in (50_001, 530_001):
+        w = configs.C5.scaled(n_params=P, n_pushes=120)
+        hip, ora = _run_both_batched(hipmod, w, [10, 33], launch_block=block, launch_grid=grid, launch_waves_per_cu=waves,
+                                     launch_alternate=alternate, launch_vec=2)
+        _compare(hip, ora, w)
+        hip.close()
 
 
 def test_batched_pushes_with_norms_timer_double_buffer_and_accumulate(hipmod):
     from paper_1509_04210_amd import binding as B
-    w = configs.C5.scaled(n_params=77_777, n_pushes=90)
-    hip, ora = _run_both_batched(hipmod, w, [7, 20], flags=B.FLAG_STATS_NORMS | B.FLAG_TIME_KERNELS | B.FLAG_DOUBLE_BUFFER)
-    _compare(hip, ora, w)
-    st, ref = hip.ps.stats(), ora.ps.norms()
-    assert st.norms_valid == 1 and st.kernel_launches == st.n_apply_launches < st.n_updates
-    for got, want in [(st.theta_sq, ref["theta_sq"]), (st.v_sq, ref["v_sq"]), (st.gbar_sq, ref["gbar_sq"])]:
-        assert abs(got - want) <= 1e-5 * want                  # norms are those of the last update of the last launch
-    assert st.theta_inf == ref["theta_inf"]
-    hip.close()
+    for P in (77_777, 600_001):
+        w = configs.C5.scaled(n_params=P, n_pushes=90)
+        hip, ora = _run_both_batched(hipmod, w, [7, 20], flags=B.FLAG_STATS_NORMS | B.FLAG_TIME_KERNELS | B.FLAG_DOUBLE_BUFFER)
+        _compare(hip, ora, w)
+        st, ref = hip.ps.stats(), ora.ps.norms()
+        assert st.norms_valid == 1 and st.kernel_launches == st.n_apply_launches < st.n_updates
+        for got, want in [(st.theta_sq, ref["theta_sq"]), (st.v_sq, ref["v_sq"]), (st.gbar_sq, ref["gbar_sq"])]:
+            assert abs(got - want) <= 1e-5 * want              # norms are those of the last update of the last launch
+        assert st.theta_inf == ref["theta_inf"]
+        hip.close()
     hip, ora = _run_both_batched(hipmod, w, [7, 20], flags=B.FLAG_PUSH_ACCUMULATE)     # the plain loop: nothing is fused
     _compare(hip, ora, w)
     assert hip.ps.stats().n_apply_launches == hip.ps.stats().n_updates
