@@ -82,10 +82,12 @@ enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second 
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
-// the same load from an address held as an integer (global address space stated explicitly)
-__device__ __forceinline__ floatx4 load_grad4_global(uint64_t p, uint64_t iv) {
-  typedef const __attribute__((address_space(1))) floatx4* global_floatx4_ptr;
-  return __builtin_nontemporal_load(reinterpret_cast<global_floatx4_ptr>(p) + iv);
+// the same load of a float4 or a float from an address held as an integer (an address that has passed through an
+// asm statement is no longer known to be global: the address space is stated explicitly)
+template <typename T>
+__device__ __forceinline__ T load_grad_global(uint64_t p, uint64_t i) {
+  typedef const __attribute__((address_space(1))) T* global_ptr;
+  return __builtin_nontemporal_load(reinterpret_cast<global_ptr>(p) + i);
 }
 __device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
 __device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return p[iv]; }
@@ -127,7 +129,7 @@ __device__ __forceinline__ void sum_gradients(const GradSet& gs, uint32_t c, con
     for (; j < c; ++j) {
       floatx4 t[V];
 #pragma unroll
-      for (int v = 0; v < V; ++v) t[v] = load_grad4_global(p_cur, iv[v]);
+      for (int v = 0; v < V; ++v) t[v] = load_grad_global<floatx4>(p_cur, iv[v]);
       const uint32_t jn = j + 1 < (uint32_t)kMaxFused ? j + 1 : j;
       uint64_t p_next = reinterpret_cast<uint64_t>(gs.p[jn]);
       float w_next = gs.w[jn];
@@ -316,11 +318,6 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
 // are those of the last update of the plan.
 //
 // A lane owns one position of type T: a float4, or, for the P % 4 tail done by workgroup 0, a single float.
-template <typename T>
-__device__ __forceinline__ T load_grad_global(uint64_t p, uint64_t i) {  // non-temporal, global address space stated
-  typedef const __attribute__((address_space(1))) T* global_ptr;
-  return __builtin_nontemporal_load(reinterpret_cast<global_ptr>(p) + i);
-}
 template <int OPT, bool DECAY, bool STATS>
 __device__ __forceinline__ void update_lane(const floatx4& s, floatx4& th, floatx4& ve, const UpdateArgs& a, Norms& n) {
   update_vec4<OPT, DECAY, STATS>(s, th, ve, a, n);

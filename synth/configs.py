@@ -88,5 +88,9 @@ C5 = Workload("C5-imagenet-lambda-softsync", 72_000_000, 54, "softsync", 54, "av
 C4_ADAGRAD = Workload("C4-imagenet-1softsync-adagrad", 72_000_000, 18, "softsync", 1, "avg_staleness", 0.01, 0.0, 0.0,
                       3600, 1e-4, SEED0 + 6, tail_per=100, tail_factor=100.0, optimizer="adagrad")
 
-ALL = {"C1": C1, "C2": C2, "C3-n1": C3(1), "C3-n2": C3(2), "C3-n4": C3(4), "C3-n30": C3(30), "C4": C4, "C5": C5,
-       "C4-adagrad": C4_ADAGRAD}
+# The 4-softsync case with 8 gradients per update instead of floor(30/4) = 7 (Eq. 5 prints the floor; a rounded
+# lambda/n is the other way to read "about 8")
+C3_N4_C8 = replace(C3(4), name="C3-cifar-4softsync-c8", c_override=8)
+
+ALL = {"C1": C1, "C2": C2, "C3-n1": C3(1), "C3-n2": C3(2), "C3-n4": C3(4), "C3-n4-c8": C3_N4_C8, "C3-n30": C3(30), "C4": C4,
+       "C5": C5, "C4-adagrad": C4_ADAGRAD}

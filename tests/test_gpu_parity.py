@@ -87,6 +87,7 @@ SMALL = {
     "C3-n1": (configs.C3(1), 50_001, 600),
     "C3-n2": (configs.C3(2), 50_002, 600),
     "C3-n4": (configs.C3(4), 50_003, 600),           # c = floor(30/4) = 7
+    "C3-n4-c8": (configs.C3_N4_C8, 50_004, 600),     # the same with 8 gradients per update (c_override)
     "C3-n30": (configs.C3(30), 50_005, 600),
     "C4": (configs.C4, 90_007, 360),                 # c = 18, heavy-tailed gradients, momentum
     "C5": (configs.C5, 90_001, 700),                 # c = 1, momentum + weight penalty, staleness up to ~100
@@ -258,7 +259,8 @@ def _sample_indices(P, seed, n_random, span=4096):
     return np.unique(np.concatenate([head, tail, rand])).astype(np.uint64)
 
 
-FULL = {"C4-adagrad": 16384, "C2": 3000, "C3-n1": 16384, "C3-n2": 16384, "C3-n4": 16384, "C3-n30": 16384, "C4": 16384, "C5": 16384}
+FULL = {"C4-adagrad": 16384, "C2": 3000, "C3-n1": 16384, "C3-n2": 16384, "C3-n4": 16384, "C3-n4-c8": 16384, "C3-n30": 16384, "C4": 16384,
+        "C5": 16384}
 
 
 @pytest.mark.parametrize("name", list(FULL))

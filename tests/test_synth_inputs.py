@@ -47,7 +47,8 @@ def test_traces_are_seeded_and_well_formed():
 
 def test_workload_table():
     c = {k: w.c for k, w in configs.ALL.items()}
-    assert c == {"C1": 4, "C2": 30, "C3-n1": 30, "C3-n2": 15, "C3-n4": 7, "C3-n30": 1, "C4": 18, "C5": 1, "C4-adagrad": 18}
+    assert c == {"C1": 4, "C2": 30, "C3-n1": 30, "C3-n2": 15, "C3-n4": 7, "C3-n4-c8": 8, "C3-n30": 1, "C4": 18, "C5": 1,
+                 "C4-adagrad": 18}
     assert configs.C4.n_params == configs.C5.n_params == 72_000_000
     l, s = configs.C2.arrival_trace(95)
     assert len(l) == 95
