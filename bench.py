@@ -238,6 +238,8 @@ def main():
         sys.exit(2)
 
     import torch
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # loads what is built; builds only on a fresh checkout
     from paper_1509_04210_amd import binding as B
     from synth import configs
     B.lib()

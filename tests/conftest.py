@@ -13,6 +13,10 @@ def pytest_configure(config):
 
 
 @pytest.fixture(scope="session", autouse=True)
-def _oracle_built():
+def _everything_built():
+    """The tests load what is built; only if an artefact is missing altogether (a fresh checkout) do they build it.
+    After a change to a source, run __graft_entry__.build() yourself."""
+    import __graft_entry__
+    __graft_entry__.ensure_built()
     import oracle
     oracle.build()
