@@ -174,7 +174,8 @@ int rudra_ps_destroy(rudra_ps_t* ps);
  *   ts       timestamp the learner obtained from rudra_ps_pull_weights
  *   learner  0..lambda-1, or -1 for anonymous (no duplicate check under hardsync)
  *   out      HOST pointer, may be NULL
- * Errors: EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, EHIP. */
+ * Errors: EINVAL, EFUTURE_TS, EHARDSYNC_STALE, EHARDSYNC_DUP, EHIP; ENOMEM if the staleness histogram cannot grow to
+ * this gradient's staleness (the message is then rejected like any other). */
 int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out);
 
 /* A run of n pushGradient messages handled in one call: the gradients that queued up at the server while it was

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <exception>
 #include <new>
 #include <vector>
 
@@ -491,8 +492,7 @@ bool is_device_range(const void* p, size_t bytes, int device) {
   return q >= lo && bytes <= size && (size_t)(q - lo) <= size - bytes;
 }
 
-void count_staleness(rudra_ps* ps, uint64_t sigma) {
-  if (sigma >= ps->hist.size()) ps->hist.resize(sigma + 1, 0);
+void count_staleness(rudra_ps* ps, uint64_t sigma) {  // the caller has made the histogram long enough
   ps->hist[sigma] += 1;
   ps->sigma_sum += sigma;
   ps->sigma_max = std::max(ps->sigma_max, sigma);
@@ -594,7 +594,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   try {
     ps->clock_cap = ps->c + (config->max_aggregate > 1 ? config->max_aggregate - 1 : 0);
     ps->open_clock.assign(ps->clock_cap, 0);
-    ps->open_grads.reserve(ps->c);
+    ps->open_grads.reserve(ps->clock_cap);  // a message stands for at least one gradient: never more than this many
     ps->seen.assign(config->n_learners, 0);
     ps->ring_ts.assign((size_t)ps->ring * ps->clock_cap, 0);
     ps->ring_count.assign(ps->ring, 0);
@@ -651,6 +651,20 @@ int rudra_ps_destroy(rudra_ps_t* ps) {
 static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t m, int32_t learner, float weight,
                   rudra_push_result_t* out) {
   const rudra_ps_config_t& cfg = ps->cfg;
+  // Whatever can fail for lack of host memory happens before any state changes: the histogram grows to the largest
+  // staleness of this message (a gradient stamped long ago makes it long), the deferral lists get their room.
+  try {
+    uint64_t worst = 0;
+    for (uint32_t j = 0; j < m; ++j) worst = std::max(worst, ps->ts_cur - ts[j]);
+    if (worst >= ps->hist.size()) ps->hist.resize(worst + 1, 0);
+    if (ps->deferring) {
+      ps->deferred_grads.reserve(ps->deferred_grads.size() + ps->open_grads.size() + 1);
+      ps->deferred.reserve(ps->deferred.size() + 1);
+    }
+  } catch (const std::exception&) {  // bad_alloc, or length_error for an absurd staleness
+    ps->n_rejected++;
+    return RUDRA_ENOMEM;
+  }
   if (!ps->control_only) {
     if (ps->accumulate) {  // sumGradients at arrival: acc = w*g, or acc = acc + w*g
       const bool weighted = weight != 1.0f || ps->open_weighted;
@@ -778,7 +792,7 @@ int rudra_ps_push_batch(rudra_ps_t* ps, const float* const* grads, const uint64_
       rc = push_one(ps, grads ? grads[i] : nullptr, ts[i], learners ? learners[i] : -1, out ? out + i : nullptr);
       if (rc != RUDRA_OK) break;  // the messages before it stay handled; this one and the rest are not
     }
-  } catch (const std::bad_alloc&) {
+  } catch (const std::exception&) {  // cannot happen: absorb reserves before it changes anything
     rc = RUDRA_ENOMEM;
     ps->failed = true;  // the protocol state is ahead of the device state: nothing more can be trusted
   }
