@@ -634,3 +634,39 @@ def test_c_abi_from_a_plain_program_matches_closed_forms(hipmod):
     assert os.path.exists(exe), f"{exe} is missing: run __graft_entry__.build()"
     r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0 and "abi gpu check ok" in r.stdout, r.stdout + r.stderr
+
+
+# ---------------------------------------------------------------- the hand-computed traces of tests/golden, on the GPU
+@pytest.mark.parametrize("name", ["A", "B", "C", "D", "E"])
+@pytest.mark.parametrize("P", [1, 261])
+def test_worked_traces_on_the_gpu(hipmod, name, P):
+    """tests/golden/worked_traces.txt (timestamps, staleness, clocks, <sigma>, rates and weights computed by hand from
+    Sec. 3.1 / Eq. 6 with dyadic numbers) replayed through the C ABI: the same fixture that pins the oracle, checked here
+    against the HIP path directly (every element of a constant vector must equal the hand value exactly)."""
+    from paper_1509_04210_amd import binding as B
+    from tests.test_oracle_protocol import _parse_traces
+    t = _parse_traces()[name]
+    dev = torch.device("cuda", 0)
+    stream = torch.cuda.Stream(device=dev)
+    init = torch.zeros(P, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    ps = B.ParameterServer(P, t["lam"], init.data_ptr(), t["n"], B.SOFTSYNC, B.LR_AVG_STALENESS, alpha0=0.5, momentum=t["m"],
+                           stream=stream.cuda_stream)
+    bufs, out = [], torch.empty(P, dtype=torch.float32, device=dev)
+    learner_ts = [0] * t["lam"]
+    for p in t["pushes"]:
+        l = p["learner"]
+        assert learner_ts[l] == p["ts"]
+        bufs.append(torch.full((P,), p["g"], dtype=torch.float32, device=dev))       # kept alive: borrowed by the server
+        torch.cuda.synchronize()
+        rc, r = ps.push_gradient(bufs[-1].data_ptr(), learner_ts[l], l)
+        assert rc == 0 and (r.staleness, r.applied, r.ts_after) == (p["sigma"], p["applied"], p["ts_after"])
+        if p["applied"]:
+            ps.pull_weights(out.data_ptr())
+            ps.sync()
+            assert bool((out == p["theta"]).all()), (out[:4].tolist(), p["theta"])
+        learner_ts[l] = ps.pull_weights(0)
+    for idx, sig, stamps in t["clocks"]:
+        ts, avg, _ = ps.vector_clock(idx)
+        assert ts == stamps and avg == sig
+    ps.destroy()
