@@ -226,6 +226,7 @@ def main():
                     help="hand the messages over this many at a time (rudra_ps_push_batch): consecutive updates share a launch; "
                          "the headline is measured with 1 (every update its own launch)")
     ap.add_argument("--waves", type=int, default=0, help="launch_waves_per_cu")
+    ap.add_argument("--params", type=int, default=0, help="run the workload's recipe at another vector length (size sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
     ap.add_argument("--calibration-copies", type=int, default=0,
@@ -248,6 +249,8 @@ def main():
     launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid,
                   launch_waves_per_cu=args.waves)
     w = configs.ALL[args.workload]
+    if args.params:
+        w = w.scaled(n_params=args.params, name=f"{w.name}@{args.params}")
     base_flags = B.FLAG_DOUBLE_BUFFER if args.double_buffer else 0
     r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, batch=args.batch, **launch)
     bytes_upd = algorithmic_bytes_per_update(w)
@@ -256,7 +259,7 @@ def main():
     ups = r["updates"] / r["wall_s"]
     kernel_ms = r["event_ms"] / r["timed_launches"]     # the timed region is back-to-back applyUpdate launches only
     achieved = bytes_upd / (kernel_ms * 1e-3) / 1e9
-    traffic = (MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else
+    traffic = (None if args.params else MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else
                MEASURED_TRAFFIC_BYTES_BATCH8.get(args.workload) if args.batch == 8 else None)
     line = {
         "metric": METRIC, "value": ups, "unit": "applyUpdates/s", "n_gpus": 1, "steps": args.steps,

@@ -30,6 +30,10 @@ constexpr uint32_t kDefaultBlock = 64;   // one wavefront per workgroup: finest 
 constexpr uint32_t kDefaultUnroll = 4;
 constexpr uint32_t kDefaultVec = 1;
 constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding load bytes per compute unit
+// Below this many parameters a launch is only a few generations of resident waves: capping the occupancy then mostly
+// idles the chip during ramp-up and tail (c = 18: 2M parameters 6040 vs 5280 GB/s uncapped vs 26 waves, 4M 6250 vs 6070;
+// from 8M on the cap wins, 6620 vs 6380).
+constexpr uint64_t kSmallVector = 6000000;
 constexpr uint32_t kDefaultClockRing = 1024;
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
 // Batched launches (measured at 72M parameters, c = 1, 4 to 64 messages per launch, and at 1.0M and 131k parameters):
@@ -580,13 +584,13 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
     //           8 waves 6.2-6.3).
     //   c > 4 with the default unroll of 1: after the first round a wave has one gradient load outstanding, and 26
     //           resident waves are best (c = 7: 6.78, c = 18: 6.41, c = 30: 6.13, c = 54: 6.22; 20 or 32 waves lose
-    //           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind).
+    //           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind); small vectors run uncapped (kSmallVector).
     //   an explicit unroll > 1 with c above it: 48/(unroll + state vectors) waves.
     const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (kernel_optimizer(*config) != rudra::kOptSgd ? 1u : 0u);
     const uint32_t waves_per_wg = ps->block / 64;
     uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
     if (ps->c <= ps->unroll) w = std::max(w, 12u);
-    else if (ps->unroll == 1) w = 26;
+    else if (ps->unroll == 1) w = config->n_params < kSmallVector ? 32 : 26;
     w = std::max(w, std::max(4u, waves_per_wg));
     ps->waves_per_cu = std::min(w, 32u);
   }
