@@ -670,3 +670,36 @@ def test_worked_traces_on_the_gpu(hipmod, name, P):
         ts, avg, _ = ps.vector_clock(idx)
         assert ts == stamps and avg == sig
     ps.destroy()
+
+
+# ---------------------------------------------------------------- randomly drawn configurations (fixed seeds)
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(hipmod, seed):
+    """Protocol, c, rate mode, optimizer, penalty, vector length, launch shape, flags and the way the messages are handed
+    over (one by one or in runs) drawn at random from a seed; every combination must give the oracle's bits."""
+    from paper_1509_04210_amd import binding as B
+    rng = np.random.default_rng(1000 + seed)
+    lam = int(rng.integers(1, 41))
+    hard = bool(rng.integers(0, 4) == 0)
+    n_split = 1 if hard else int(rng.integers(1, lam + 1))
+    optimizer = "adagrad" if rng.integers(0, 4) == 0 else "sgd"
+    momentum = 0.0 if optimizer == "adagrad" or rng.integers(0, 2) == 0 else float(rng.choice([0.5, 0.9, 0.99]))
+    lr_mode = str(rng.choice(["const", "static_n", "avg_staleness", "per_gradient"]))
+    base = configs.C2 if hard else configs.C3(1)
+    w = _with(base, name=f"random-{seed}", n_params=int(rng.choice([1, 3, 64, 255, 4097, 20_001, 131_075])), n_learners=lam,
+              n_split=n_split, protocol="hardsync" if hard else "softsync", lr_mode=lr_mode, momentum=momentum,
+              weight_decay=float(rng.choice([0.0, 5e-4])), optimizer=optimizer, adagrad_eps=float(rng.choice([1e-8, 1e-3])),
+              alpha0=float(rng.choice([0.001, 0.01, 0.1])), n_pushes=int(rng.integers(1, 6)) * lam + int(rng.integers(0, lam)),
+              tail_per=int(rng.choice([0, 100])), straggler_prob=float(rng.choice([0.0, 0.2])), seed=int(rng.integers(1, 1 << 30)))
+    flags = int(rng.choice([0, 0, B.FLAG_DOUBLE_BUFFER, B.FLAG_PUSH_ACCUMULATE, B.FLAG_TIME_KERNELS | B.FLAG_CHECK_POINTERS]))
+    unroll = int(rng.choice([0, 1, 2, 4]))
+    launch = dict(launch_block=int(rng.choice([0, 64, 256, 1024])), launch_unroll=unroll,
+                  launch_vec=int(rng.choice([0, 1, 2])) if unroll != 4 else 0, launch_grid=int(rng.choice([0, 0, 1, 5])),
+                  launch_waves_per_cu=int(rng.choice([0, 2, 13, 32])), launch_alternate=int(rng.choice([0, 1, 2])))
+    if rng.integers(0, 2):
+        chunks = [int(x) for x in rng.integers(1, 3 * w.c + 2, size=5)]
+        hip, ora = _run_both_batched(hipmod, w, chunks, flags=flags, **launch)
+    else:
+        hip, ora = _run_both(hipmod, w, flags=flags, **launch)
+    _compare(hip, ora, w)
+    hip.close()
