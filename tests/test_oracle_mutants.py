@@ -39,6 +39,14 @@ MUTANTS = {
     "adagrad_eps_inside_the_root": ("real denom = root + (real)o->cfg.adagrad_eps;", "real denom = (real)sqrt((double)o->vel[k] + (double)o->cfg.adagrad_eps);"),
     "adagrad_penalty_after_accumulator": ("      real sq = gbar * gbar;", "      real sq = (gbar - wd * o->theta[k]) * (gbar - wd * o->theta[k]);"),
     "timestamp_in_clock_is_staleness": ("o->open_clock[o->count] = ts;", "o->open_clock[o->count] = sigma;"),
+    "future_timestamp_accepted": ("  if (ts > o->ts_cur) { o->n_rejected++; return OR_EFUTURE_TS; }       /* ts_j >= ts_i */", ""),
+    "mean_by_division": ("real gbar = o->acc[k] * inv_c;", "real gbar = o->acc[k] / (real)o->count; (void)inv_c;"),
+    "timestamp_advances_per_gradient": ("  o->ts_cur += 1;                                  /* each weight update increments the timestamp */",
+                                        "  o->ts_cur += o->count;"),
+    "contributors_not_forgotten_after_the_step": ("  memset(o->seen, 0, o->cfg.n_learners);", ""),
+    "caller_factor_ignored": ("double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;", "double lr = (double)o->cfg.alpha0;"),
+    "histogram_counts_timestamps": ("  int rc = count_staleness(o, sigma);", "  int rc = count_staleness(o, ts);"),
+    "adagrad_root_of_the_mean_square": ("      real denom = root + (real)o->cfg.adagrad_eps;", "      real denom = root / (real)sqrt((double)(o->n_updates + 1)) + (real)o->cfg.adagrad_eps;"),
 }
 
 
