@@ -108,7 +108,9 @@ typedef struct {
   uint32_t launch_grid;   /* upper bound on workgroups (grid-stride beyond it); 0 = one tile per workgroup */
   uint32_t launch_waves_per_cu; /* cap on resident wavefronts per compute unit, 2..32 (enforced by reserving LDS per
                                    workgroup); 0 = library default.  Fewer resident waves keep fewer DRAM pages open
-                                   at once; see the kernel header for the measured optimum. */
+                                   at once; see the kernel header for the measured optimum.  The hardware hands out
+                                   LDS in coarse units, so neighbouring values can give the same occupancy (measured:
+                                   21..25 behave alike, 26..31 behave alike). */
   uint32_t max_aggregate;    /* largest number of learner gradients one rudra_ps_push_aggregate message may stand for
                                 (0 or 1: relayed averages are not used).  An update can then collect up to
                                 c + max_aggregate - 1 gradients. */
