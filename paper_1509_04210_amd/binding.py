@@ -123,6 +123,8 @@ class ParameterServer:
         self._h = h
         self.n_params = n_params
         self._res = PushResult()
+        self._res_ref = C.byref(self._res)
+        self._push = self._L.rudra_ps_push_gradient
 
     def destroy(self):
         if getattr(self, "_h", None):
@@ -133,8 +135,7 @@ class ParameterServer:
 
     def push_gradient(self, grad_ptr, ts, learner=-1):
         """(status, PushResult).  The PushResult object is reused by the next call."""
-        rc = self._L.rudra_ps_push_gradient(self._h, grad_ptr or None, ts, learner, C.byref(self._res))
-        return rc, self._res
+        return self._push(self._h, grad_ptr or None, ts, learner, self._res_ref), self._res
 
     def push_batch(self, grad_ptrs, ts_list, learners=None):
         """rudra_ps_push_batch: a run of messages in one call.  (status, n_handled, [PushResult] * n_handled)."""
