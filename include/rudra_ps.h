@@ -57,7 +57,7 @@ enum rudra_optimizer {
 enum rudra_flags {
   RUDRA_FLAG_STATS_NORMS = 1u,     /* every applyUpdate also reduces ||gbar||^2, ||theta||^2, ||theta||_inf, ||v||^2 */
   RUDRA_FLAG_PUSH_ACCUMULATE = 2u, /* sum each gradient into a server-owned accumulator at push time (the literal
-                                      "receive and accumulate" of Sec. 2); the caller's buffer is free again as
+                                      accumulate-on-arrival reading of sumGradients in Sec. 2); the caller's buffer is free again as
                                       soon as work it enqueues later on the stream runs.  Same bits as the default. */
   RUDRA_FLAG_CONTROL_ONLY = 4u,    /* timestamps, staleness, clocks and rates only: no device memory, no kernels;
                                       grad may be NULL; pulling weights is an error.  For host-side tests. */
@@ -203,7 +203,7 @@ int rudra_ps_push_batch(rudra_ps_t* ps, const float* const* grads, const uint64_
 /* The root of a parameter-server tree (Sec. 3.3) receiving what a node relays: avg = the average of m learner
  * gradients (see rudra_ps_leaf_mean), with the m timestamps of those gradients (HOST pointer ts) so that staleness,
  * vector clock and <sigma> stay exact.  It counts as m gradients: the running sum takes m*avg, applyUpdate fires once
- * at least c gradients are in ("at least c", Sec. 3.1) and averages over the number collected.  The paper does not
+ * c or more gradients are in (Sec. 3.1) and averages over the number collected.  The paper does not
  * say which timestamp a relayed average carries nor when a node relays: this is this library's reading.
  * avg: DEVICE pointer, borrowed like a pushed gradient.  out->staleness = the largest constituent staleness.
  * Errors: EINVAL (m = 0, m > max_aggregate, RUDRA_LR_PER_GRADIENT, bad pointer), EFUTURE_TS, EHARDSYNC_STALE, EHIP. */

@@ -30,11 +30,11 @@
  *                  staleness always zero (Sec. 3.1, Eq. 3)
  *   n-softsync     update after c = floor(lambda/n) gradients, averaged
  *                  (Sec. 3.1, Eq. 5); n = lambda is the async rule (Eq. 4)
- *   sumGradients   receive and accumulate (Sec. 2)
+ *   sumGradients   gradients are added up as they come in (Sec. 2)
  *   applyUpdate    multiply the accumulated gradient by the learning rate and
  *                  update the weights (Sec. 2, Eq. 1c)
  *   learning rate  hardsync: alpha0 times a caller-known factor sqrt(lambda*mu/B);
- *                  softsync: alpha0 times the reciprocal of staleness,
+ *                  softsync: alpha0 divided by the staleness,
  *                  alpha = alpha0/<sigma> = alpha0/n (Sec. 3.2, Sec. 5.1 Eq. 6)
  *   momentum 0.9, weight penalty 5e-4: named, no formula printed (Sec. 4.2).
  *   AdaGrad: named for the ImageNet 1-softsync runs (Sec. 5.5), no formula or epsilon printed.
@@ -43,7 +43,7 @@
  *   - the divisor of the staleness-modulated rate is max(1, <sigma>): the paper's
  *     hardsync rule divides by nothing and n >= 1, so the rate is never raised
  *     above alpha0 and <sigma> = 0 cannot divide;
- *   - "at least c gradients": messages arrive one at a time, so the update fires
+ *   - the update needs c gradients or more: messages arrive one at a time, so it fires
  *     when the count reaches exactly c;
  *   - gradients are added in arrival order, the first one initialising the sum;
  *   - the average is sum * (1/c), with 1/c rounded once to the working precision;
@@ -51,7 +51,7 @@
  *     velocity, the convention of the networks the paper says it follows);
  *   - weight penalty: L2, gbar <- gbar + wd*theta before rate and momentum;
  *   - tree of servers (Sec. 3.3): a node relays (g_1+...+g_k)*(1/k) together with its constituents' timestamps;
- *     the root adds m*avg for a message standing for m gradients, fires at "at least c" and divides by the
+ *     the root adds m*avg for a message standing for m gradients, fires once c or more are in and divides by the
  *     number collected (the paper says neither which timestamp a relayed average carries nor when a node relays);
  *   - per-gradient modulation (Sec. 5.1 footnote, not explored by the paper):
  *     each arriving gradient is scaled by 1/max(1, sigma_l) before it is added;
@@ -263,7 +263,7 @@ static void apply_update(oracle_t *o, real lr) {
 static int maybe_update(oracle_t *o, int *applied, float *lr_used) {
   *applied = 0;
   *lr_used = 0.0f;
-  if (o->count < o->c) return OR_OK;               /* "at least c gradients" (Sec. 3.1) */
+  if (o->count < o->c) return OR_OK;               /* fewer than c so far: wait (Sec. 3.1) */
   /* <sigma> = (i-1) - mean(i_1..i_count) with i-1 = ts_cur, i.e. mean of (ts_cur - i_k), Eq. 2 */
   const double avg_sigma = (double)o->sigma_sum_open / (double)o->count;
   double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;
@@ -310,7 +310,7 @@ int FN(push)(oracle_t *o, const float *grad, uint64_t ts, int32_t learner, oracl
   }
   const uint64_t sigma = staleness_of(o, ts);
 
-  /* sumGradients: receive and accumulate, in arrival order */
+  /* sumGradients: every arriving gradient is added to the running sum, in arrival order */
   const uint64_t P = o->cfg.n_params;
   if (o->cfg.lr_mode == LR_PER_GRADIENT) {
     /* Sec. 5.1 footnote: a staler gradient gets a smaller rate */

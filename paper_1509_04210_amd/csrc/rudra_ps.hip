@@ -692,7 +692,7 @@ static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t 
 
   int applied = 0;
   float lr_used = 0.f;
-  if (ps->count >= ps->c) {  // "at least c gradients": exactly c unless a relayed average overshoots
+  if (ps->count >= ps->c) {  // c or more gradients are in: exactly c unless a relayed average overshoots
     // <sigma> of this update: mean over its clock of (ts_cur - ts_k) = (i-1) - mean(i_k), Eq. 2
     const double avg_sigma = (double)ps->sigma_sum_open / (double)ps->count;
     double lr = (double)cfg.alpha0 * (double)cfg.lr_scale;
