@@ -17,7 +17,7 @@
  *   - Calls on one server are serialised by an internal mutex: the order of
  *     rudra_ps_push_gradient calls IS the arrival order of the gradients, and it
  *     fixes the order of the floating-point additions (Sec. 3.2 "Parameter Server":
- *     the server handles incoming messages one by one).
+ *     the server takes its messages one at a time).
  *   - All device work is enqueued on the caller's stream; push never waits for the GPU.
  */
 #ifndef RUDRA_PS_H
@@ -181,7 +181,7 @@ int rudra_ps_destroy(rudra_ps_t* ps);
 int rudra_ps_push_gradient(rudra_ps_t* ps, const float* grad, uint64_t ts, int32_t learner, rudra_push_result_t* out);
 
 /* A run of n pushGradient messages handled in one call: the gradients that queued up at the server while it was
- * busy (Sec. 3.2: learners send with blocking calls and the server takes the messages one by one).  Message i is
+ * busy (Sec. 3.2: learners send with blocking calls and the server takes the messages one at a time).  Message i is
  * (grads[i], ts[i], learners[i]); the protocol state (staleness, vector clocks, rates, timestamps, statistics, rejections)
  * is exactly what n calls of rudra_ps_push_gradient in this order would leave, and so are theta and v, bit for bit.
  * What differs is the device work: consecutive updates completed inside the call are applied by ONE launch that

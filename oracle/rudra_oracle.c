@@ -27,7 +27,7 @@
  *   vector clock   the timestamps of the gradients that trigger update i-1 -> i;
  *                  <sigma> = (i-1) - mean(i_1..i_c)  (Sec. 3.1, Eq. 2 "avg staleness")
  *   hardsync       exactly one gradient per learner per step, all lambda averaged,
- *                  staleness always zero (Sec. 3.1, Eq. 3)
+ *                  so sigma = 0 for every gradient (Sec. 3.1, Eq. 3)
  *   n-softsync     update after c = floor(lambda/n) gradients, averaged
  *                  (Sec. 3.1, Eq. 5); n = lambda is the async rule (Eq. 4)
  *   sumGradients   gradients are added up as they come in (Sec. 2)
@@ -274,7 +274,7 @@ static int maybe_update(oracle_t *o, int *applied, float *lr_used) {
   apply_update(o, lr_work);
   int rc = log_update(o, avg_sigma, *lr_used);
   if (rc != OR_OK) return rc;
-  o->ts_cur += 1;                                  /* each weight update increments the timestamp */
+  o->ts_cur += 1;                                  /* the timestamp counts the weight updates (Sec. 3.1) */
   o->count = 0;
   o->sigma_sum_open = 0;
   memset(o->seen, 0, o->cfg.n_learners);
@@ -305,7 +305,7 @@ int FN(push)(oracle_t *o, const float *grad, uint64_t ts, int32_t learner, oracl
   if (learner < -1 || learner >= (int32_t)o->cfg.n_learners) { o->n_rejected++; return OR_EINVAL; }
   if (ts > o->ts_cur) { o->n_rejected++; return OR_EFUTURE_TS; }       /* ts_j >= ts_i */
   if (o->cfg.protocol == PROTO_HARDSYNC) {
-    if (ts != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; } /* staleness is always zero */
+    if (ts != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; } /* sigma must be 0 under hardsync */
     if (learner >= 0 && o->seen[learner]) { o->n_rejected++; return OR_EHARDSYNC_DUP; } /* exactly one */
   }
   const uint64_t sigma = staleness_of(o, ts);

@@ -720,7 +720,7 @@ static int absorb(rudra_ps* ps, const float* grad, const uint64_t* ts, uint32_t 
     ps->last_avg = avg_sigma;
     ps->last_lr = lr_used;
     ps->n_updates += 1;
-    ps->ts_cur += 1;  // each weight update increments the timestamp
+    ps->ts_cur += 1;  // the timestamp counts the weight updates (Sec. 3.1)
     ps->count = 0;
     ps->sigma_sum_open = 0;
     ps->open_weighted = false;

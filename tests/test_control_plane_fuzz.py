@@ -73,7 +73,7 @@ def test_random_message_sequences(lam, data):
 
 
 def test_concurrent_pushes_are_serialised():
-    """The server handles messages one by one (Sec. 3.2): 8 threads pushing at once lose no message and every update
+    """The server takes its messages one at a time (Sec. 3.2): 8 threads pushing at once lose no message and every update
     has exactly c entries."""
     lam, c, per_thread = 8, 4, 2000
     ps = R.ParameterServer(1, lam, 0, 2, B.SOFTSYNC, B.LR_AVG_STALENESS, flags=B.FLAG_CONTROL_ONLY)

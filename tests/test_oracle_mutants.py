@@ -41,7 +41,7 @@ MUTANTS = {
     "timestamp_in_clock_is_staleness": ("o->open_clock[o->count] = ts;", "o->open_clock[o->count] = sigma;"),
     "future_timestamp_accepted": ("  if (ts > o->ts_cur) { o->n_rejected++; return OR_EFUTURE_TS; }       /* ts_j >= ts_i */", ""),
     "mean_by_division": ("real gbar = o->acc[k] * inv_c;", "real gbar = o->acc[k] / (real)o->count; (void)inv_c;"),
-    "timestamp_advances_per_gradient": ("  o->ts_cur += 1;                                  /* each weight update increments the timestamp */",
+    "timestamp_advances_per_gradient": ("  o->ts_cur += 1;                                  /* the timestamp counts the weight updates (Sec. 3.1) */",
                                         "  o->ts_cur += o->count;"),
     "contributors_not_forgotten_after_the_step": ("  memset(o->seen, 0, o->cfg.n_learners);", ""),
     "caller_factor_ignored": ("double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;", "double lr = (double)o->cfg.alpha0;"),

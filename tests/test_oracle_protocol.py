@@ -190,7 +190,7 @@ def test_rejections_change_nothing():
     assert ps.push(g, 1, 0)[0] == oracle.EFUTURE_TS               # a gradient cannot come from the future
     assert ps.push(g, 0, 3)[0] == oracle.EINVAL                   # no such learner
     assert ps.push(g, 0, 0)[0] == 0
-    assert ps.push(g, 0, 0)[0] == oracle.EHARDSYNC_DUP            # exactly one mini-batch per learner per step
+    assert ps.push(g, 0, 0)[0] == oracle.EHARDSYNC_DUP            # a learner contributes once per step
     assert ps.push(g, 0, 1)[0] == 0
     assert ps.pending == 2 and ps.n_pushes == 2 and ps.n_rejected == 3
     rc, r = ps.push(g, 0, 2)
