@@ -840,7 +840,10 @@ int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params,
   const uint64_t tiles = (n4 + block - 1) / block;
   uint64_t grid = tiles ? tiles : 1;
   if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
-  const LaunchShape shape = {(uint32_t)grid, block, tiles, 0};
+  // resident waves per CU (measured at 72M parameters, 4 loads at a time per lane): k = 2 uncapped 6.62 TB/s; k = 3: 16 waves
+  // 6.57 (uncapped 6.40); k = 6: 12 waves 6.65 (6.25); k = 18: 8 waves 6.52 (5.92)
+  const uint32_t waves = (k <= 2 || n_params < kSmallVector) ? 32u : k == 3 ? 16u : k <= 8 ? 12u : 8u;
+  const LaunchShape shape = {(uint32_t)grid, block, tiles, lds_for_occupancy(waves, block)};
   UpdateArgs a;
   std::memset(&a, 0, sizeof(a));
   a.sum_out = out;
@@ -856,8 +859,8 @@ int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params,
     while (n < (uint32_t)kMaxFused && first < k) { gs.p[n] = grads[first++]; gs.w[n] = 1.0f; ++n; }
     a.c = n;
     a.inv_c = (first == k) ? 1.0f / (float)k : 1.0f;  // (g_1 + ... + g_k) * (1/k): scaled once, at the end
-    if (first == k) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, true, 4, 1>), dim3(shape.grid), dim3(shape.block), 0, (hipStream_t)stream, gs, a);
-    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 1>), dim3(shape.grid), dim3(shape.block), 0, (hipStream_t)stream, gs, a);
+    if (first == k) hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, true, 4, 1>), dim3(shape.grid), dim3(shape.block), shape.lds_bytes, (hipStream_t)stream, gs, a);
+    else hipLaunchKernelGGL((rudra::sum_gradients_kernel<false, false, 4, 1>), dim3(shape.grid), dim3(shape.block), shape.lds_bytes, (hipStream_t)stream, gs, a);
     if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
     have_head = true;
   }
