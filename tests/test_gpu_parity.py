@@ -703,3 +703,29 @@ def test_random_configurations(hipmod, seed):
         hip, ora = _run_both(hipmod, w, flags=flags, **launch)
     _compare(hip, ora, w)
     hip.close()
+
+
+# ---------------------------------------------------------------- bench.py keeps its contract
+def test_bench_prints_one_json_line_with_the_agreed_fields(hipmod):
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "8", "--warmup", "2", "--no-extra", "--no-cpu-baseline"],
+                       capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    j = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling", "vs_baseline",
+                "dtype", "data", "config", "roofline"):
+        assert key in j, key
+    assert j["n_gpus"] == 1 and j["steps"] == 8 and j["warmup"] == 2 and j["dtype"] == "f32" and j["vs_baseline"] is None
+    assert "workload" in j["config"] and "model" not in j["config"]
+    roof = j["roofline"]
+    assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12 and 0.3 < roof["frac"] < 1.0
+    assert abs(j["value"] * j["ms_per_step"] / 1e3 - 1.0) < 1e-9          # value = steps / wall time
+    r2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r2.returncode != 0 and "ONE GPU" in r2.stderr
