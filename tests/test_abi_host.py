@@ -216,3 +216,18 @@ def test_set_lr_changes_later_updates_only():
     ps.set_lr(0.05)
     assert np.float32(ps.push_gradient(0, 1, 0)[1].lr_used) == np.float32(0.05)
     assert ps.vector_clock(0)[2] == 0.5
+
+
+@pytest.mark.parametrize("lam,n", [(1000, 1), (1000, 16), (1000, 1000), (4097, 64)])
+def test_many_learners(lam, n):
+    """Learner counts far beyond the workloads' (c = 1000, 62, 1, 64): control plane against the oracle."""
+    from dataclasses import replace
+    w = replace(configs.C3(1), name="many", n_learners=lam, n_split=n, n_pushes=3 * lam + 17, straggler_prob=0.05)
+    learner, step = w.arrival_trace()
+    hip, ora = _Control(w, clock_ring=8192), _OracleControl(w)
+    lh = replay.replay(hip, learner, step, w.n_learners)
+    lo = replay.replay(ora, learner, step, w.n_learners)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    _same_protocol_state(hip, ora)
+    assert hip.ps.stats().c == lam // n

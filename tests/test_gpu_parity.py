@@ -729,3 +729,17 @@ def test_bench_prints_one_json_line_with_the_agreed_fields(hipmod):
     assert abs(j["value"] * j["ms_per_step"] / 1e3 - 1.0) < 1e-9          # value = steps / wall time
     r2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
     assert r2.returncode != 0 and "ONE GPU" in r2.stderr
+
+
+# ---------------------------------------------------------------- many learners: c far beyond one launch's 64 pointers
+@pytest.mark.parametrize("lam,n,batched", [(1000, 1, False), (1000, 16, False), (300, 1, True), (1000, 16, True)])
+def test_many_learners_on_the_gpu(hipmod, lam, n, batched):
+    """c = 1000 (fifteen folds of 64 into the accumulator, then the fused launch), 62 (one launch) and 300, also handed
+    over in runs that span several updates."""
+    w = _with(configs.C3(1).scaled(n_params=2_051, n_pushes=2 * lam + 40), n_learners=lam, n_split=n, momentum=0.9, weight_decay=5e-4)
+    if batched:
+        hip, ora = _run_both_batched(hipmod, w, [lam // n + 9, 3 * (lam // n)], ring=4 * lam + 16)
+    else:
+        hip, ora = _run_both(hipmod, w)
+    _compare(hip, ora, w)
+    hip.close()
