@@ -18,7 +18,9 @@
  *     rudra_ps_push_gradient calls IS the arrival order of the gradients, and it
  *     fixes the order of the floating-point additions (Sec. 3.2 "Parameter Server":
  *     the server takes its messages one at a time).
- *   - All device work is enqueued on the caller's stream; push never waits for the GPU.
+ *   - All device work is enqueued on the caller's stream; push never waits for the GPU and never allocates device
+ *     memory (everything is allocated by rudra_ps_create).  One exception, by request: with RUDRA_FLAG_TIME_KERNELS
+ *     a push waits for the oldest timed launch once 256 timed launches are outstanding.
  */
 #ifndef RUDRA_PS_H
 #define RUDRA_PS_H
@@ -61,7 +63,9 @@ enum rudra_flags {
                                       soon as work it enqueues later on the stream runs.  Same bits as the default. */
   RUDRA_FLAG_CONTROL_ONLY = 4u,    /* timestamps, staleness, clocks and rates only: no device memory, no kernels;
                                       grad may be NULL; pulling weights is an error.  For host-side tests. */
-  RUDRA_FLAG_TIME_KERNELS = 8u,    /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t */
+  RUDRA_FLAG_TIME_KERNELS = 8u,    /* bracket every applyUpdate launch with HIP events; see rudra_ps_stats_t.  A measuring
+                                      mode: the events live in a ring of 256, so the push that triggers a launch while 256
+                                      earlier ones are still unresolved waits for the oldest of them to finish */
   RUDRA_FLAG_DOUBLE_BUFFER = 16u,  /* keep two weight buffers: update i reads one and writes the other (no extra traffic),
                                       so the weights of timestamp ts stay readable while update ts+1 runs: the
                                       computation-buffer / communication-buffer pair with a pointer swap of Sec. 3.3,
@@ -86,12 +90,13 @@ enum rudra_status {
 typedef struct {
   uint64_t n_params;     /* P, number of fp32 parameters (> 0) */
   uint32_t n_learners;   /* lambda (> 0) */
-  uint32_t n_split;      /* n of n-softsync, 1..lambda; ignored under hardsync */
+  uint32_t n_split;      /* n of n-softsync, 1..lambda; under hardsync only RUDRA_LR_STATIC_N reads it (then >= 1) */
   uint32_t c_override;   /* 0: c = lambda (hardsync) or floor(lambda/n) (softsync); else gradients per update */
   int32_t protocol;      /* enum rudra_protocol */
   int32_t lr_mode;       /* enum rudra_lr_mode */
   float alpha0;          /* base learning rate */
-  float lr_scale;        /* caller-known factor, e.g. sqrt(lambda*mu/B); use 1 when none */
+  float lr_scale;        /* caller-known factor, e.g. sqrt(lambda*mu/B); 1 when there is none.  0 is rejected (EINVAL):
+                            a zero-initialised config would otherwise freeze the weights without a word */
   float momentum;        /* 0 = plain SGD; else v <- m v - alpha gbar, theta <- theta + v (Sec. 4.2: 0.9) */
   float weight_decay;    /* L2 penalty: gbar <- gbar + wd*theta (Sec. 4.2: 5e-4 on ImageNet) */
   int32_t optimizer;     /* enum rudra_optimizer */
@@ -99,7 +104,8 @@ typedef struct {
   int32_t device;        /* HIP device ordinal */
   uint32_t flags;        /* OR of enum rudra_flags */
   void* stream;          /* hipStream_t, borrowed from the caller (NULL = the device's null stream) */
-  uint32_t clock_ring;   /* closed vector clocks kept for rudra_ps_vector_clock (0 = 1024) */
+  uint32_t clock_ring;   /* closed vector clocks kept for rudra_ps_vector_clock (0 = 1024); c + max_aggregate - 1 may be at
+                            most 2^24 and clock_ring times that at most 2^27 timestamps (EINVAL beyond) */
   /* launch shape of the fused kernel; 0 = library default.  Results do not depend on it, except the order in
      which the optional norms are reduced. */
   uint32_t launch_block;  /* threads per workgroup: 64..1024, multiple of 64 */
@@ -154,6 +160,8 @@ typedef struct {
   uint64_t n_weight_views;  /* rudra_ps_weights_view calls */
   uint64_t n_apply_launches;  /* applyUpdate kernel launches: equals n_updates unless rudra_ps_push_batch fused some */
   uint64_t n_batched_updates; /* updates that shared a launch with at least one other update */
+  uint64_t n_weight_acquires; /* rudra_ps_weights_acquire calls */
+  uint64_t n_reader_waits;    /* reader events that applyUpdate launches were made to wait for (rudra_ps_weights_release) */
 } rudra_ps_stats_t;
 
 /* Create a server.  init_weights: DEVICE pointer to P floats (checked with the HIP runtime), copied (the caller keeps its buffer); in
@@ -206,7 +214,10 @@ int rudra_ps_push_batch(rudra_ps_t* ps, const float* const* grads, const uint64_
  * c or more gradients are in (Sec. 3.1) and averages over the number collected.  The paper does not
  * say which timestamp a relayed average carries nor when a node relays: this is this library's reading.
  * avg: DEVICE pointer, borrowed like a pushed gradient.  out->staleness = the largest constituent staleness.
- * Errors: EINVAL (m = 0, m > max_aggregate, RUDRA_LR_PER_GRADIENT, bad pointer), EFUTURE_TS, EHARDSYNC_STALE, EHIP. */
+ * Under hardsync exactly lambda gradients make a step (Eq. 3): a message that would carry the count past lambda is
+ * rejected with EHARDSYNC_DUP (some learner would be counted twice).
+ * Errors: EINVAL (m = 0, m > max_aggregate, RUDRA_LR_PER_GRADIENT, bad pointer), EFUTURE_TS, EHARDSYNC_STALE,
+ * EHARDSYNC_DUP, EHIP. */
 int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts, uint32_t m, rudra_push_result_t* out);
 
 /* The arithmetic of a non-root node of the tree (Sec. 3.3: it averages the gradients sent from its learners and relays
@@ -228,7 +239,32 @@ int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out);
  * for the caller. */
 int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_out);
 
-/* Copy of the momentum velocity v (DEVICE pointer to P floats), enqueued on the stream. */
+/* The same view for a reader on ANOTHER stream, with the ordering made explicit: the communication-buffer side of the
+ * computation/communication buffer pair of Sec. 3.3 (a learner's pull thread copies weights while the computation goes on).
+ *   rudra_ps_weights_acquire  makes `reader_stream` (hipStream_t of the same device; may be NULL = null stream) wait
+ *       for the work on the server's stream that produces the weights of the current timestamp, and returns their
+ *       DEVICE pointer, the timestamp and a ticket.  The caller then enqueues its reads (copies, kernels) on
+ *       reader_stream.
+ *   rudra_ps_weights_release  announces that all those reads have been enqueued on reader_stream: the applyUpdate
+ *       launch that overwrites this buffer is made to wait (on the device; no host call blocks) until they are done.
+ * The buffer is overwritten by the FIRST applyUpdate launch enqueued after the acquire, or, with
+ * RUDRA_FLAG_DOUBLE_BUFFER, by the SECOND (the first only reads it), so with two buffers the reads overlap the next update
+ * instead of delaying it.  Release must come before that launch is enqueued; if it comes too late it returns ESTATE and
+ * the reads may have seen a torn buffer (the caller should acquire again).  A ticket that is never released
+ * protects nothing.  theta_out, ts_out (may be NULL), ticket_out: HOST pointers.
+ * Errors: EINVAL, ESTATE (CONTROL_ONLY; release too late), ENOMEM, EHIP. */
+int rudra_ps_weights_acquire(rudra_ps_t* ps, void* reader_stream, const float** theta_out, uint64_t* ts_out, uint64_t* ticket_out);
+int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_stream);
+
+/* The launch shape the next single-update launch (batched = 0) or batched launch (batched != 0) would use: workgroups,
+ * threads per workgroup, tiles of the vector (more than the workgroups when the grid is capped: grid-stride), LDS
+ * bytes reserved per workgroup as the occupancy cap.  Pure host arithmetic (works in CONTROL_ONLY mode): grid * block
+ * always stays below 2^32, the most one HIP launch takes.  HOST pointers, each may be NULL. */
+int rudra_ps_launch_shape(rudra_ps_t* ps, int32_t batched, uint32_t* grid_out, uint32_t* block_out, uint64_t* ntiles_out,
+                          uint32_t* lds_bytes_out);
+
+/* Copy of the second state vector (the momentum velocity v, or AdaGrad's h) to dst (DEVICE pointer to P floats),
+ * enqueued on the stream.  ESTATE when the update rule keeps none (plain SGD, momentum = 0). */
 int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst);
 
 /* Counters and staleness statistics the server records (Sec. 3.2: it records the vector clock of each update to

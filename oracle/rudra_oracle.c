@@ -159,6 +159,8 @@ int FN(create)(const oracle_config *cfg, const float *init_weights, oracle_t **o
   if (cfg->lr_mode < LR_CONST || cfg->lr_mode > LR_PER_GRADIENT) return OR_EINVAL;
   if (cfg->protocol == PROTO_SOFTSYNC && (cfg->n_split < 1 || cfg->n_split > cfg->n_learners))
     return OR_EINVAL;
+  if (cfg->lr_mode == LR_STATIC_N && cfg->n_split < 1) return OR_EINVAL; /* alpha0/n (Eq. 6) needs n >= 1 */
+  if (cfg->lr_scale == 0.0f) return OR_EINVAL;   /* the caller-known factor multiplies alpha0: 1 when there is none */
   if (gradients_per_update(cfg) == 0) return OR_EINVAL;
   if (cfg->optimizer != OPT_SGD && cfg->optimizer != OPT_ADAGRAD) return OR_EINVAL;
   if (cfg->optimizer == OPT_ADAGRAD && (cfg->momentum != 0.0f || !(cfg->adagrad_eps >= 0.0f))) return OR_EINVAL;
@@ -362,6 +364,9 @@ int FN(push_aggregate)(oracle_t *o, const float *avg, const uint64_t *ts, uint32
   if (!o || !avg || !ts || m == 0) return OR_EINVAL;
   const uint32_t max_m = o->cfg.max_aggregate > 1 ? o->cfg.max_aggregate : 1;
   if (m > max_m || o->cfg.lr_mode == LR_PER_GRADIENT) { o->n_rejected++; return OR_EINVAL; }
+  /* hardsync: exactly one gradient from each of the lambda learners is averaged (Sec. 3.1, Eq. 3), so a relayed
+   * average may complete the step but never overshoot it; "c or more" is the n-softsync trigger (Eq. 5) */
+  if (o->cfg.protocol == PROTO_HARDSYNC && (uint64_t)o->count + m > o->c) { o->n_rejected++; return OR_EHARDSYNC_DUP; }
   for (uint32_t j = 0; j < m; ++j) {
     if (ts[j] > o->ts_cur) { o->n_rejected++; return OR_EFUTURE_TS; }
     if (o->cfg.protocol == PROTO_HARDSYNC && ts[j] != o->ts_cur) { o->n_rejected++; return OR_EHARDSYNC_STALE; }

@@ -44,7 +44,8 @@ class Stats(C.Structure):
                 ("kernel_launches", C.c_uint64), ("pending", C.c_uint32), ("c", C.c_uint32),
                 ("last_lr", C.c_float), ("norms_valid", C.c_int32), ("last_hip_error", C.c_int32),
                 ("reserved", C.c_uint32), ("n_weight_copies", C.c_uint64), ("n_ts_inquiries", C.c_uint64),
-                ("n_weight_views", C.c_uint64), ("n_apply_launches", C.c_uint64), ("n_batched_updates", C.c_uint64)]
+                ("n_weight_views", C.c_uint64), ("n_apply_launches", C.c_uint64), ("n_batched_updates", C.c_uint64),
+                ("n_weight_acquires", C.c_uint64), ("n_reader_waits", C.c_uint64)]
 
 
 _lib = None
@@ -69,6 +70,9 @@ def lib():
             "rudra_ps_leaf_mean": [C.POINTER(vp), u32, u64, vp, i32, vp],
             "rudra_ps_pull_weights": [vp, vp, C.POINTER(u64)],
             "rudra_ps_weights_view": [vp, C.POINTER(vp), C.POINTER(u64)],
+            "rudra_ps_weights_acquire": [vp, vp, C.POINTER(vp), C.POINTER(u64), C.POINTER(u64)],
+            "rudra_ps_weights_release": [vp, u64, vp],
+            "rudra_ps_launch_shape": [vp, i32, C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(u32)],
             "rudra_ps_pull_velocity": [vp, vp],
             "rudra_ps_stats": [vp, C.POINTER(Stats)],
             "rudra_ps_staleness_hist": [vp, C.POINTER(u64), u64, C.POINTER(u64)],
@@ -169,6 +173,26 @@ class ParameterServer:
         if rc != OK:
             raise RudraError(rc, "rudra_ps_weights_view")
         return p.value, ts.value
+
+    def weights_acquire(self, reader_stream=0):
+        """(device address of the current weights, their timestamp, ticket) for reads enqueued on `reader_stream`."""
+        p, ts, ticket = C.c_void_p(), C.c_uint64(), C.c_uint64()
+        rc = self._L.rudra_ps_weights_acquire(self._h, reader_stream or None, C.byref(p), C.byref(ts), C.byref(ticket))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_weights_acquire")
+        return p.value, ts.value, ticket.value
+
+    def weights_release(self, ticket, reader_stream=0):
+        """The C status: OK, or ESTATE when the buffer's overwriting launch was already enqueued."""
+        return self._L.rudra_ps_weights_release(self._h, ticket, reader_stream or None)
+
+    def launch_shape(self, batched=False):
+        """(grid, block, ntiles, lds_bytes) of the next single-update or batched launch."""
+        g, b, t, l = C.c_uint32(), C.c_uint32(), C.c_uint64(), C.c_uint32()
+        rc = self._L.rudra_ps_launch_shape(self._h, int(batched), C.byref(g), C.byref(b), C.byref(t), C.byref(l))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_launch_shape")
+        return g.value, b.value, t.value, l.value
 
     def pull_velocity(self, dst_ptr):
         rc = self._L.rudra_ps_pull_velocity(self._h, dst_ptr)

@@ -35,6 +35,8 @@ constexpr uint32_t kInFlightKiBPerCu = 48;  // measured optimum of outstanding l
 // from 8M on the cap wins, 6620 vs 6380).
 constexpr uint64_t kSmallVector = 6000000;
 constexpr uint32_t kDefaultClockRing = 1024;
+constexpr uint64_t kMaxClockEntries = 1ull << 24;  // gradients one update may collect (c + max_aggregate - 1)
+constexpr uint64_t kMaxRingEntries = 1ull << 27;   // timestamps the ring of closed clocks may hold (1 GiB of host memory)
 constexpr uint32_t kTimerRing = 256;  // event pairs in flight in TIME_KERNELS mode
 // Batched launches (measured at 72M parameters, c = 1, 4 to 64 messages per launch, and at 1.0M and 131k parameters):
 // 26 resident waves are best or equal everywhere (16: -3 to -12 %, 32: -1 to -3 %): between two loads a wave does a
@@ -134,6 +136,12 @@ struct rudra_ps {
   std::vector<Pending> deferred_grads;
   std::vector<DeferredUpdate> deferred;
 
+  // readers of a weight buffer on other streams (rudra_ps_weights_acquire / _release)
+  std::vector<hipEvent_t> free_events;         // created on demand, reused
+  std::vector<hipEvent_t> reader_done[2];      // per weight buffer: reads the next launch that writes it must wait for
+  size_t n_reader_events = 0;                  // events in existence (in one of the three lists, or in a caller's hand)
+  uint64_t n_weight_acquires = 0, n_reader_waits = 0;
+
   // kernel timing
   std::vector<hipEvent_t> ev_start, ev_stop;
   uint64_t timed_launches = 0, timed_resolved = 0;
@@ -184,14 +192,42 @@ uint32_t lds_for_occupancy(uint32_t waves_per_cu, uint32_t block) {
   return bytes > kMaxDynamicLds ? kMaxDynamicLds : bytes;
 }
 
+// Workgroups for `tiles` tiles: one per tile, at least one (the scalar tail needs workgroup 0), at most `cap` when
+// the caller set one, and never so many that grid * block reaches 2^32 (HIP rejects such a launch); the kernels walk
+// the remaining tiles with a grid-stride loop.
+uint32_t grid_for(uint64_t tiles, uint32_t block, uint32_t cap) {
+  uint64_t grid = tiles ? tiles : 1;
+  if (cap && grid > cap) grid = cap;
+  const uint64_t most = 0xFFFFFFFFull / block;
+  if (grid > most) grid = most;
+  return (uint32_t)grid;
+}
+
+// Resident wavefronts per CU for the single-update kernel when the caller names none.
+// Measured at 72M parameters (GB/s of algorithmic bytes, medians): what counts is how many loads are in flight per
+// CU, about kInFlightKiBPerCu KiB at 1 KiB per wave-load, and, at equal volume, that few tiles are open at once.
+//   c <= unroll (4): a wave issues theta, the second state vector and all its gradients in one round; 48/(loads per
+//           wave) resident waves, at least 12 (c = 1: 16 waves 7.0 TB/s; c = 2: 12 waves 7.0; c = 4: 12 waves 6.7-6.8,
+//           8 waves 6.2-6.3).
+//   c > 4 with the default unroll of 1: after the first round a wave has one gradient load outstanding, and 26
+//           resident waves are best (c = 7: 6.78, c = 18: 6.41, c = 30: 6.13, c = 54: 6.22; 20 or 32 waves lose
+//           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind); small vectors run uncapped (kSmallVector).
+//   an explicit unroll > 1 with c above it: 48/(unroll + state vectors) waves.
+uint32_t default_waves_per_cu(uint32_t c, uint32_t unroll, int optimizer, uint64_t n_params, uint32_t block) {
+  const uint32_t per_wave = std::min(c, unroll) + 1u + (optimizer != rudra::kOptSgd ? 1u : 0u);
+  const uint32_t waves_per_wg = block / 64;
+  uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
+  if (c <= unroll) w = std::max(w, 12u);
+  else if (unroll == 1) w = n_params < kSmallVector ? 32 : 26;
+  w = std::max(w, std::max(4u, waves_per_wg));
+  return std::min(w, 32u);
+}
+
 LaunchShape shape_for(const rudra_ps* ps) {
   const uint64_t n4 = ps->cfg.n_params >> 2;
   const uint64_t tile = (uint64_t)ps->block * ps->vec;
-  uint64_t tiles = (n4 + tile - 1) / tile;
-  uint64_t grid = tiles ? tiles : 1;  // the scalar tail still needs workgroup 0
-  if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
-  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;  // grid-stride covers the rest
-  return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(ps->waves_per_cu, ps->block)};
+  const uint64_t tiles = (n4 + tile - 1) / tile;
+  return {grid_for(tiles, ps->block, ps->grid_cap), ps->block, tiles, lds_for_occupancy(ps->waves_per_cu, ps->block)};
 }
 
 // ---- kernel dispatch: runtime (optimizer, decay, weighted, stats, unroll, vec) -> template instance ----
@@ -254,7 +290,7 @@ UpdateArgs base_args(const rudra_ps* ps) {
   UpdateArgs a;
   std::memset(&a, 0, sizeof(a));
   a.theta = ps->theta2[ps->cur];
-  a.theta_out = ps->theta2[ps->double_buffer ? (ps->cur ^ 1u) : ps->cur];
+  a.theta_out = ps->theta2[ps->double_buffer ? (ps->cur ^ 1u) : ps->cur];  // = write_buffer(ps)
   a.vel = ps->vel;
   a.sum_out = ps->acc;
   a.partials = ps->partials;
@@ -265,13 +301,9 @@ UpdateArgs base_args(const rudra_ps* ps) {
   return a;
 }
 
-int ensure_acc(rudra_ps* ps) {
-  if (ps->acc) return RUDRA_OK;
-  hipError_t e = hipMalloc((void**)&ps->acc, ps->cfg.n_params * sizeof(float));
-  if (e == hipErrorOutOfMemory) { ps->last_hip_error = (int)e; return RUDRA_ENOMEM; }
-  if (e != hipSuccess) return hip_fail(ps, e);
-  return RUDRA_OK;
-}
+// The accumulator is allocated by rudra_ps_create whenever an update can hold more than kMaxFused messages, so
+// that no push ever allocates.
+int ensure_acc(rudra_ps* ps) { return ps->acc ? RUDRA_OK : RUDRA_ESTATE; }
 
 // acc <- sum of `n` entries of `g` (which may start with acc itself), arrival order kept.
 int enqueue_sum(rudra_ps* ps, const Pending* g, uint32_t n, bool weighted) {
@@ -316,6 +348,45 @@ int end_timed(rudra_ps* ps, uint32_t slot) {
   return RUDRA_OK;
 }
 
+// An event for ordering against a reader's stream: from the free list, or a new one (no timing data kept).
+int take_event(rudra_ps* ps, hipEvent_t* ev) {
+  if (!ps->free_events.empty()) {
+    *ev = ps->free_events.back();
+    ps->free_events.pop_back();
+    return RUDRA_OK;
+  }
+  // Room for every event that exists is reserved in all three lists before the event is made, so that handing an
+  // event from one list to another never allocates (and so never throws).
+  try {
+    const size_t n = ps->n_reader_events + 1;
+    ps->free_events.reserve(n);
+    ps->reader_done[0].reserve(n);
+    ps->reader_done[1].reserve(n);
+  } catch (const std::exception&) {
+    return RUDRA_ENOMEM;
+  }
+  RUDRA_HIP(ps, hipEventCreateWithFlags(ev, hipEventDisableTiming));
+  ps->n_reader_events += 1;
+  return RUDRA_OK;
+}
+
+// The launch about to be enqueued writes weight buffer `buf`: it must not start before the reads that
+// rudra_ps_weights_release has announced for that buffer are done.  The wait is on the device (the server's stream
+// waits for the readers' events); the host does not block.
+int wait_for_readers(rudra_ps* ps, uint32_t buf) {
+  std::vector<hipEvent_t>& done = ps->reader_done[buf];
+  for (hipEvent_t ev : done) {
+    RUDRA_HIP(ps, hipStreamWaitEvent(ps->stream, ev, 0));
+    ps->n_reader_waits += 1;
+  }
+  // an event may be recorded again once the wait on it has been enqueued: the wait refers to the record before it
+  ps->free_events.insert(ps->free_events.end(), done.begin(), done.end());
+  done.clear();
+  return RUDRA_OK;
+}
+
+uint32_t write_buffer(const rudra_ps* ps) { return ps->double_buffer ? (ps->cur ^ 1u) : ps->cur; }
+
 // Bookkeeping common to every applyUpdate launch: walk direction, double-buffer pointer swap.
 void after_apply_launch(rudra_ps* ps, uint32_t grid) {
   ps->last_apply_blocks = grid;
@@ -357,7 +428,9 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
   const LaunchShape s = shape_for(ps);
   a.ntiles = s.ntiles;
   uint32_t slot = 0;
-  int rc = begin_timed(ps, &slot);
+  int rc = wait_for_readers(ps, write_buffer(ps));
+  if (rc != RUDRA_OK) return rc;
+  rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
   launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
   RUDRA_HIP(ps, hipGetLastError());
@@ -406,11 +479,8 @@ void launch_batch(int opt, bool decay, bool weighted, bool stats, LaunchShape s,
 LaunchShape batch_shape_for(const rudra_ps* ps) {
   const uint64_t npos = ps->cfg.n_params >> 2;
   const uint64_t tiles = (npos + ps->block - 1) / ps->block;
-  uint64_t grid = tiles ? tiles : 1;
-  if (ps->grid_cap && grid > ps->grid_cap) grid = ps->grid_cap;
-  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
   const uint32_t waves = ps->cfg.launch_waves_per_cu ? ps->cfg.launch_waves_per_cu : std::max(kBatchWavesPerCu, ps->block / 64);
-  return {(uint32_t)grid, ps->block, tiles, lds_for_occupancy(waves, ps->block)};
+  return {grid_for(tiles, ps->block, ps->grid_cap), ps->block, tiles, lds_for_occupancy(waves, ps->block)};
 }
 
 // Enqueue the updates `d[0..n_upd)` (consuming consecutive entries of `g`) as ONE batched launch.  Caller guarantees
@@ -436,7 +506,9 @@ int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint3
   const LaunchShape s = batch_shape_for(ps);
   a.ntiles = s.ntiles;
   uint32_t slot = 0;
-  int rc = begin_timed(ps, &slot);
+  int rc = wait_for_readers(ps, write_buffer(ps));
+  if (rc != RUDRA_OK) return rc;
+  rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
   launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, s, ps->stream, gs, plan, a);
   RUDRA_HIP(ps, hipGetLastError());
@@ -507,7 +579,15 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->protocol != RUDRA_HARDSYNC && c->protocol != RUDRA_SOFTSYNC) return RUDRA_EINVAL;
   if (c->lr_mode < RUDRA_LR_CONST || c->lr_mode > RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;
   if (c->protocol == RUDRA_SOFTSYNC && (c->n_split < 1 || c->n_split > c->n_learners)) return RUDRA_EINVAL;
+  if (c->lr_mode == RUDRA_LR_STATIC_N && c->n_split < 1) return RUDRA_EINVAL;  // alpha0/n needs n >= 1 under hardsync too
+  if (c->lr_scale == 0.0f) return RUDRA_EINVAL;  // a zeroed config would freeze the weights silently: 1 means "no factor"
   if (gradients_per_update(*c) == 0) return RUDRA_EINVAL;
+  {
+    // an update collects at most c + max_aggregate - 1 timestamps; the ring keeps that many per closed clock
+    const uint64_t cap = (uint64_t)gradients_per_update(*c) + (c->max_aggregate > 1 ? c->max_aggregate - 1 : 0);
+    const uint64_t ring = c->clock_ring ? c->clock_ring : kDefaultClockRing;
+    if (cap > kMaxClockEntries || ring > kMaxRingEntries / cap) return RUDRA_EINVAL;
+  }
   if (c->optimizer != RUDRA_OPT_SGD && c->optimizer != RUDRA_OPT_ADAGRAD) return RUDRA_EINVAL;
   if (c->optimizer == RUDRA_OPT_ADAGRAD && (c->momentum != 0.0f || !(c->adagrad_eps >= 0.0f))) return RUDRA_EINVAL;
   if (c->launch_block && (c->launch_block < 64 || c->launch_block > 1024 || c->launch_block % 64)) return RUDRA_EINVAL;
@@ -535,6 +615,9 @@ void release(rudra_ps* ps) {
     (void)hipStreamSynchronize(ps->stream);
     for (hipEvent_t e : ps->ev_start) (void)hipEventDestroy(e);
     for (hipEvent_t e : ps->ev_stop) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ps->free_events) (void)hipEventDestroy(e);
+    for (int b = 0; b < 2; ++b)
+      for (hipEvent_t e : ps->reader_done[b]) (void)hipEventDestroy(e);
     if (ps->theta2[0]) (void)hipFree(ps->theta2[0]);
     if (ps->theta2[1]) (void)hipFree(ps->theta2[1]);
     if (ps->vel) (void)hipFree(ps->vel);
@@ -574,29 +657,11 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   if (config->launch_vec) ps->vec = config->launch_vec;
   ps->grid_cap = config->launch_grid;
   ps->alternate = config->launch_alternate != 2;
-  if (config->launch_waves_per_cu) {
-    ps->waves_per_cu = config->launch_waves_per_cu;
-  } else {
-    // Measured at 72M parameters (GB/s of algorithmic bytes, medians): what counts is how many loads are in flight per
-    // CU, about kInFlightKiBPerCu KiB at 1 KiB per wave-load, and, at equal volume, that few tiles are open at once.
-    //   c <= 4: a wave issues theta, the second state vector and all its gradients in one round; 48/(loads per wave)
-    //           resident waves, at least 12 (c = 1: 16 waves 7.0 TB/s; c = 2: 12 waves 7.0; c = 4: 12 waves 6.7-6.8,
-    //           8 waves 6.2-6.3).
-    //   c > 4 with the default unroll of 1: after the first round a wave has one gradient load outstanding, and 26
-    //           resident waves are best (c = 7: 6.78, c = 18: 6.41, c = 30: 6.13, c = 54: 6.22; 20 or 32 waves lose
-    //           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind); small vectors run uncapped (kSmallVector).
-    //   an explicit unroll > 1 with c above it: 48/(unroll + state vectors) waves.
-    const uint32_t per_wave = std::min(ps->c, ps->unroll) + 1u + (kernel_optimizer(*config) != rudra::kOptSgd ? 1u : 0u);
-    const uint32_t waves_per_wg = ps->block / 64;
-    uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
-    if (ps->c <= ps->unroll) w = std::max(w, 12u);
-    else if (ps->unroll == 1) w = config->n_params < kSmallVector ? 32 : 26;
-    w = std::max(w, std::max(4u, waves_per_wg));
-    ps->waves_per_cu = std::min(w, 32u);
-  }
+  ps->waves_per_cu = config->launch_waves_per_cu ? config->launch_waves_per_cu
+                                                 : default_waves_per_cu(ps->c, ps->unroll, kernel_optimizer(*config), config->n_params, ps->block);
   ps->ring = config->clock_ring ? config->clock_ring : kDefaultClockRing;
   try {
-    ps->clock_cap = ps->c + (config->max_aggregate > 1 ? config->max_aggregate - 1 : 0);
+    ps->clock_cap = ps->c + (config->max_aggregate > 1 ? config->max_aggregate - 1 : 0);  // bounded by validate_config
     ps->open_clock.assign(ps->clock_cap, 0);
     ps->open_grads.reserve(ps->clock_cap);  // a message stands for at least one gradient: never more than this many
     ps->seen.assign(config->n_learners, 0);
@@ -605,7 +670,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
     ps->ring_avg.assign(ps->ring, 0.0);
     ps->ring_lr.assign(ps->ring, 0.f);
     ps->hist.reserve(64);
-  } catch (const std::bad_alloc&) {
+  } catch (const std::exception&) {  // bad_alloc, length_error
     delete ps;
     return RUDRA_ENOMEM;
   }
@@ -619,10 +684,13 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
     }
     if (e == hipSuccess) e = hipMalloc((void**)&ps->theta2[0], bytes);
     if (e == hipSuccess && ps->double_buffer) e = hipMalloc((void**)&ps->theta2[1], bytes);
-    if (e == hipSuccess) e = hipMalloc((void**)&ps->vel, bytes);
-    if (e == hipSuccess && ps->accumulate) e = hipMalloc((void**)&ps->acc, bytes);
+    // the second state vector (velocity, or AdaGrad's h) exists only when the rule has one; the accumulator only
+    // when gradients are summed at arrival or an update can hold more messages than one launch takes
+    const bool second_state = kernel_optimizer(*config) != rudra::kOptSgd;
+    if (e == hipSuccess && second_state) e = hipMalloc((void**)&ps->vel, bytes);
+    if (e == hipSuccess && (ps->accumulate || ps->clock_cap > (uint32_t)kMaxFused)) e = hipMalloc((void**)&ps->acc, bytes);
     if (e == hipSuccess) e = hipMemcpyAsync(ps->theta2[0], init_weights, bytes, hipMemcpyDeviceToDevice, ps->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(ps->vel, 0, bytes, ps->stream);
+    if (e == hipSuccess && second_state) e = hipMemsetAsync(ps->vel, 0, bytes, ps->stream);
     if (e == hipSuccess && ps->want_norms) {
       ps->partials_blocks = std::max(shape_for(ps).grid, batch_shape_for(ps).grid);
       e = hipMalloc((void**)&ps->partials, (size_t)ps->partials_blocks * kNumNorms * sizeof(double));
@@ -821,6 +889,9 @@ int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts
   if (rc != RUDRA_OK) { ps->n_rejected++; return rc; }
   const uint32_t max_m = cfg.max_aggregate > 1 ? cfg.max_aggregate : 1;
   if (m > max_m || cfg.lr_mode == RUDRA_LR_PER_GRADIENT) { ps->n_rejected++; return RUDRA_EINVAL; }
+  // hardsync averages exactly one gradient from each of the lambda learners (Eq. 3): a relayed average may complete
+  // the step but not overshoot it (the "c or more" trigger belongs to n-softsync, Eq. 5)
+  if (cfg.protocol == RUDRA_HARDSYNC && (uint64_t)ps->count + m > ps->c) { ps->n_rejected++; return RUDRA_EHARDSYNC_DUP; }
   for (uint32_t j = 0; j < m; ++j) {
     if (ts[j] > ps->ts_cur) { ps->n_rejected++; return RUDRA_EFUTURE_TS; }
     if (cfg.protocol == RUDRA_HARDSYNC && ts[j] != ps->ts_cur) { ps->n_rejected++; return RUDRA_EHARDSYNC_STALE; }
@@ -838,12 +909,11 @@ int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params,
   const uint64_t n4 = n_params >> 2;
   const uint32_t block = kDefaultBlock;
   const uint64_t tiles = (n4 + block - 1) / block;
-  uint64_t grid = tiles ? tiles : 1;
-  if (grid > 0x7FFFFFFFull) grid = 0x7FFFFFFFull;
+  const uint32_t grid = grid_for(tiles, block, 0);
   // resident waves per CU (measured at 72M parameters, 4 loads at a time per lane): k = 2 uncapped 6.62 TB/s; k = 3: 16 waves
   // 6.57 (uncapped 6.40); k = 6: 12 waves 6.65 (6.25); k = 18: 8 waves 6.52 (5.92)
   const uint32_t waves = (k <= 2 || n_params < kSmallVector) ? 32u : k == 3 ? 16u : k <= 8 ? 12u : 8u;
-  const LaunchShape shape = {(uint32_t)grid, block, tiles, lds_for_occupancy(waves, block)};
+  const LaunchShape shape = {grid, block, tiles, lds_for_occupancy(waves, block)};
   UpdateArgs a;
   std::memset(&a, 0, sizeof(a));
   a.sum_out = out;
@@ -895,10 +965,73 @@ int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_
   return RUDRA_OK;
 }
 
+int rudra_ps_weights_acquire(rudra_ps_t* ps, void* reader_stream, const float** theta_out, uint64_t* ts_out, uint64_t* ticket_out) {
+  if (!ps || !theta_out || !ticket_out) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
+  if ((hipStream_t)reader_stream != ps->stream) {
+    // the weights of ts_cur are produced by work already on the server's stream: the reader's stream waits for it
+    hipEvent_t ready;
+    int rc = take_event(ps, &ready);
+    if (rc != RUDRA_OK) return rc;
+    hipError_t e = hipEventRecord(ready, ps->stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent((hipStream_t)reader_stream, ready, 0);
+    ps->free_events.push_back(ready);
+    RUDRA_HIP(ps, e);
+  }
+  *theta_out = ps->theta2[ps->cur];
+  if (ts_out) *ts_out = ps->ts_cur;
+  // the ticket names the buffer and the launch count at which it was handed out
+  *ticket_out = (ps->n_apply_launches << 1) | ps->cur;
+  ps->n_weight_acquires += 1;
+  return RUDRA_OK;
+}
+
+int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_stream) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  const uint64_t seq = ticket >> 1;
+  const uint32_t buf = (uint32_t)(ticket & 1u);
+  if (seq > ps->n_apply_launches || (buf == 1 && !ps->double_buffer)) return RUDRA_EINVAL;
+  // the launch that overwrites the buffer is the first one after the acquire (one buffer) or the second (two)
+  const uint64_t lifetime = ps->double_buffer ? 2 : 1;
+  if (ps->n_apply_launches - seq >= lifetime) return RUDRA_ESTATE;  // too late: that launch is already enqueued
+  if ((hipStream_t)reader_stream == ps->stream) return RUDRA_OK;    // stream order already protects the reads
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
+  hipEvent_t done;
+  int rc = take_event(ps, &done);
+  if (rc != RUDRA_OK) return rc;
+  hipError_t e = hipEventRecord(done, (hipStream_t)reader_stream);
+  if (e != hipSuccess) {
+    ps->free_events.push_back(done);
+    return hip_fail(ps, e);
+  }
+  ps->reader_done[buf].push_back(done);  // room was reserved when the event was created
+  return RUDRA_OK;
+}
+
+int rudra_ps_launch_shape(rudra_ps_t* ps, int32_t batched, uint32_t* grid_out, uint32_t* block_out, uint64_t* ntiles_out,
+                          uint32_t* lds_bytes_out) {
+  if (!ps) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  const LaunchShape s = batched ? batch_shape_for(ps) : shape_for(ps);
+  if (grid_out) *grid_out = s.grid;
+  if (block_out) *block_out = s.block;
+  if (ntiles_out) *ntiles_out = s.ntiles;
+  if (lds_bytes_out) *lds_bytes_out = s.lds_bytes;
+  return RUDRA_OK;
+}
+
 int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst) {
   if (!ps || !dst) return RUDRA_EINVAL;
   std::lock_guard<std::mutex> lock(ps->mu);
-  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->control_only || !ps->vel) return RUDRA_ESTATE;  // plain SGD keeps no second state vector
   if (ps->failed) return RUDRA_EHIP;
   DeviceGuard guard(ps->cfg.device);
   RUDRA_HIP(ps, guard.error());
@@ -929,6 +1062,8 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
   out->n_weight_views = ps->n_weight_views;
   out->n_apply_launches = ps->n_apply_launches;
   out->n_batched_updates = ps->n_batched_updates;
+  out->n_weight_acquires = ps->n_weight_acquires;
+  out->n_reader_waits = ps->n_reader_waits;
   if (ps->failed) return RUDRA_EHIP;
   if (ps->time_kernels) {
     DeviceGuard guard(ps->cfg.device);

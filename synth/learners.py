@@ -1,16 +1,17 @@
 """Emulated learners feeding one ParameterServer on one GPU.
 
-Harness used by the GPU tests, smoke() and bench.py: torch supplies device memory and the
-stream, synth supplies the seeded gradients (generated on the device) and the arrival trace,
-and every step of the update path itself runs inside the HIP library.
+Harness used by the GPU tests, smoke() and bench.py (not part of the library's package): torch
+supplies device memory and the stream, synth supplies the seeded gradients (generated on the
+device) and the arrival trace, and every step of the update path itself runs inside the HIP
+library, reached through its ctypes binding.  Holds none of the method's arithmetic.
 """
 from __future__ import annotations
 
 import torch
 
-from synth import gradgen
+from paper_1509_04210_amd import binding as B
 
-from . import binding as B
+from . import gradgen
 
 PROTOCOL = {"hardsync": B.HARDSYNC, "softsync": B.SOFTSYNC}
 LR_MODE = {"const": B.LR_CONST, "static_n": B.LR_STATIC_N, "avg_staleness": B.LR_AVG_STALENESS,

@@ -1,0 +1,275 @@
+"""More GPU parity cases, through the C ABI, against the CPU oracle: the whole 72M-element vector compared element by
+element, the weighted fold path (per-gradient weights with more gradients than one launch takes), relayed averages
+combined with every server flag, and a reader on a second stream that copies the weights of one timestamp while later
+updates are enqueued (the computation / communication buffer pair of Sec. 3.3)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.adapter import LR_MODE, OPTIMIZER, PROTOCOL, OracleServer
+from oracle import OraclePS
+from synth import configs, gradgen, replay
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def hipmod():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1509_04210_amd import binding
+    from synth import learners
+    binding.lib()            # fails loudly if the HIP library is not built
+    gradgen.device_lib()
+    return learners
+
+
+def _with(w, **kw):
+    return type(w)(**{**w.__dict__, **kw})
+
+
+# ---------------------------------------------------------------- the full 72M-element vector, element by element
+class _FullVectorOracle:
+    """The oracle on ALL n_params elements.  The gradient of (learner, step) is generated on the device by the input
+    generator (whose bit identity with the numpy generator is tested separately) and copied to the host, because hashing
+    72M elements per gradient in numpy would take minutes; the arithmetic is the oracle's alone."""
+
+    def __init__(self, w):
+        self.w = w
+        self.buf = torch.empty(w.n_params, dtype=torch.float32, device="cuda")
+        self.host = torch.empty(w.n_params, dtype=torch.float32, pin_memory=True)
+        self.ps = OraclePS(self._vector(w.init_key(), w.init_std, 0), w.n_learners, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode],
+                           w.alpha0, w.lr_scale, w.momentum, w.weight_decay, w.c_override, optimizer=OPTIMIZER[w.optimizer],
+                           adagrad_eps=w.adagrad_eps)
+
+    def _vector(self, key, std, tail_per):
+        gradgen.fill_device(self.buf.data_ptr(), self.w.n_params, key, std, tail_per, self.w.tail_factor, stream=0)
+        torch.cuda.synchronize()
+        self.host.copy_(self.buf)
+        torch.cuda.synchronize()
+        return self.host.numpy()
+
+    def push(self, learner, step, ts):
+        w = self.w
+        rc, res = self.ps.push(self._vector(w.grad_key(learner, step), w.grad_std, w.tail_per), ts, learner)
+        return rc, int(res.staleness), int(res.applied)
+
+    def pull_ts(self):
+        return self.ps.ts
+
+
+@pytest.mark.parametrize("name,n_pushes", [("C4", 18 * 3), ("C5", 20)])
+def test_full_vector_parity_at_72m(hipmod, name, n_pushes):
+    """The two 72M-parameter workloads in the launch shape bench.py times, a short stretch of their traces (C4: three
+    applyUpdates of 18 heavy-tailed gradients with momentum; C5: twenty single-gradient updates with momentum and weight
+    penalty), theta and v compared over ALL 72 000 000 elements: within 1e-5 * ||.||_inf, and bit for bit."""
+    w = configs.ALL[name].scaled(n_pushes=n_pushes)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w), _FullVectorOracle(w)
+    lh = replay.replay(hip, learner, step, w.n_learners)
+    lo = replay.replay(ora, learner, step, w.n_learners)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    assert ora.ps.ts == n_pushes // w.c == hip.pull_ts()
+    for got, ref, what in ((hip.weights(), ora.ps.theta, "theta"), (hip.velocity(), ora.ps.velocity, "v")):
+        got = got.cpu().numpy()
+        assert got.shape == ref.shape == (72_000_000,)
+        err = np.abs(got.astype(np.float64) - ref).max()
+        assert err <= TOL * np.abs(ref).max(), f"{what}: max abs err {err:.3e}"
+        assert np.array_equal(got, ref), f"{what} not bit-identical over the whole vector"
+    hip.close()
+    torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------- weighted fold path: per-gradient weights, c > 64
+@pytest.mark.parametrize("c,batched", [(65, False), (130, False), (200, True)])
+def test_per_gradient_weights_with_more_gradients_than_one_launch_takes(hipmod, c, batched):
+    """Sec. 5.1 footnote mode with c beyond the 64 pointers of one launch: the leading groups are folded into the
+    accumulator WITH their staleness weights, the rest goes through the weighted fused kernel."""
+    w = _with(configs.C3(1).scaled(n_params=6_007, n_pushes=3 * c + 5), n_learners=c, lr_mode="per_gradient", momentum=0.9,
+              weight_decay=5e-4, straggler_prob=0.3)
+    learner, step = w.arrival_trace()
+    ora = OracleServer(w)
+    if batched:
+        hip = hipmod.HipServer(w, ring=4 * c + 16)
+        chunks = [c // 2 + 3, 2 * c]
+        lh = replay.replay_batched(hip, learner, step, w.n_learners, chunks)
+        lo = replay.replay_batched(ora, learner, step, w.n_learners, chunks)
+    else:
+        hip = hipmod.HipServer(w)
+        lh = replay.replay(hip, learner, step, w.n_learners)
+        lo = replay.replay(ora, learner, step, w.n_learners)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    assert lo["staleness"].max() >= 2                  # some weights really differ from 1
+    assert np.array_equal(hip.weights().cpu().numpy(), ora.ps.theta)
+    assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
+    assert hip.ps.stats().ts_cur == ora.ps.ts == 3
+    hip.close()
+
+
+def test_relayed_averages_with_more_messages_than_one_launch_takes(hipmod):
+    """A root that collects 70 relayed averages of 2 gradients per update (c = 140): the fold path with message weights."""
+    lam, fan_in = 140, 2
+    w = _with(configs.C3(1).scaled(n_params=3_001, n_pushes=lam * 3), n_learners=lam, momentum=0.9)
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, ring=2 * fan_in + 2, avg_ring=lam // fan_in + 4, max_aggregate=fan_in)
+    ora = OracleServer(w, max_aggregate=fan_in)
+    lh = replay.replay_tree(hip, learner, step, lam, fan_in)
+    lo = replay.replay_tree(ora, learner, step, lam, fan_in)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    assert ora.ps.ts >= 2
+    assert np.array_equal(hip.weights().cpu().numpy(), ora.ps.theta)
+    assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
+    hip.close()
+
+
+# ---------------------------------------------------------------- the tree root under every flag, randomly drawn
+def _compare_tree(hip, ora, w):
+    th = hip.weights().cpu().numpy()
+    assert np.abs(th.astype(np.float64) - ora.ps.theta).max() <= TOL * max(np.abs(ora.ps.theta).max(), 1e-30)
+    assert np.array_equal(th, ora.ps.theta)
+    if w.momentum != 0 or w.optimizer == "adagrad":
+        assert np.array_equal(hip.velocity().cpu().numpy(), ora.ps.velocity)
+    st, o = hip.ps.stats(), ora.ps
+    assert (st.ts_cur, st.n_pushes, st.pending, st.sigma_sum, st.sigma_max) == (o.ts, o.n_pushes, o.pending, o.sigma_sum, o.sigma_max)
+    assert np.array_equal(np.array(hip.ps.staleness_hist(), np.uint64), o.hist)
+    clocks, avg, lr = o.clocks, o.avg_staleness, o.lr_log
+    for u in range(o.n_updates):
+        t, a, r = hip.ps.vector_clock(u)
+        assert t == [int(x) for x in clocks[u]] and a == avg[u] and np.float32(r) == lr[u]
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_tree_configurations(hipmod, seed):
+    """rudra_ps_push_aggregate with protocol, fan-in, c, rate mode, optimizer, penalty, vector length, launch shape and
+    server flags (accumulate at push, double buffer, fused norms, timer, pointer check) drawn from a seed."""
+    from paper_1509_04210_amd import binding as B
+    rng = np.random.default_rng(5000 + seed)
+    fan_in = int(rng.integers(2, 6))
+    hard = bool(rng.integers(0, 4) == 0)
+    lam = fan_in * int(rng.integers(1, 9)) if hard else int(rng.integers(fan_in, 41))      # hardsync: every node fills
+    n_split = 1 if hard else int(rng.integers(1, max(2, lam // fan_in)))
+    optimizer = "adagrad" if rng.integers(0, 4) == 0 else "sgd"
+    momentum = 0.0 if optimizer == "adagrad" or rng.integers(0, 2) == 0 else float(rng.choice([0.5, 0.9]))
+    base = configs.C2 if hard else configs.C3(1)
+    w = _with(base, name=f"random-tree-{seed}", n_params=int(rng.choice([3, 255, 4097, 20_001, 131_075])), n_learners=lam,
+              n_split=n_split, protocol="hardsync" if hard else "softsync", lr_mode=str(rng.choice(["const", "static_n", "avg_staleness"])),
+              momentum=momentum, weight_decay=float(rng.choice([0.0, 5e-4])), optimizer=optimizer,
+              alpha0=float(rng.choice([0.001, 0.01, 0.1])), n_pushes=int(rng.integers(2, 6)) * lam + int(rng.integers(0, lam)),
+              tail_per=int(rng.choice([0, 100])), straggler_prob=float(rng.choice([0.0, 0.2])), seed=int(rng.integers(1, 1 << 30)))
+    flags = [0, B.FLAG_PUSH_ACCUMULATE, B.FLAG_DOUBLE_BUFFER, B.FLAG_STATS_NORMS, B.FLAG_DOUBLE_BUFFER | B.FLAG_STATS_NORMS,
+             B.FLAG_PUSH_ACCUMULATE | B.FLAG_STATS_NORMS | B.FLAG_DOUBLE_BUFFER, B.FLAG_TIME_KERNELS | B.FLAG_CHECK_POINTERS,
+             B.FLAG_PUSH_ACCUMULATE | B.FLAG_DOUBLE_BUFFER][seed % 8]
+    launch = dict(launch_block=int(rng.choice([0, 64, 256])), launch_unroll=int(rng.choice([0, 1, 2])),
+                  launch_grid=int(rng.choice([0, 0, 5])), launch_waves_per_cu=int(rng.choice([0, 13, 32])),
+                  launch_alternate=int(rng.choice([0, 1, 2])))
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, flags=flags, ring=2 * fan_in + 2, avg_ring=w.c // fan_in + fan_in + 4, max_aggregate=fan_in, **launch)
+    ora = OracleServer(w, max_aggregate=fan_in)
+    lh = replay.replay_tree(hip, learner, step, lam, fan_in, hardsync=hard)
+    lo = replay.replay_tree(ora, learner, step, lam, fan_in, hardsync=hard)
+    for k in lo:
+        assert np.array_equal(lh[k], lo[k]), k
+    assert ora.ps.ts >= 1
+    _compare_tree(hip, ora, w)
+    if flags & B.FLAG_STATS_NORMS:
+        st, ref = hip.ps.stats(), ora.ps.norms()
+        assert st.norms_valid == 1
+        for got, want in [(st.theta_sq, ref["theta_sq"]), (st.v_sq, ref["v_sq"]), (st.gbar_sq, ref["gbar_sq"])]:
+            assert abs(got - want) <= 1e-5 * max(want, 1e-30)
+        assert st.theta_inf == ref["theta_inf"]
+    hip.close()
+
+
+def test_plain_sgd_keeps_no_velocity(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = configs.C1.scaled(n_params=4099, n_pushes=8)
+    hip = hipmod.HipServer(w)
+    dst = torch.empty(w.n_params, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.RudraError) as e:
+        hip.ps.pull_velocity(dst.data_ptr())
+    assert e.value.status == B.ESTATE
+    hip.close()
+
+
+# ---------------------------------------------------------------- concurrent pull: a reader on another stream
+def _slow_work(stream, big_a, big_b, reps):
+    """Keeps `stream` busy for tens of milliseconds (plain device copies of a large tensor)."""
+    with torch.cuda.stream(stream):
+        for _ in range(reps):
+            big_b.copy_(big_a)
+
+
+@pytest.mark.parametrize("double_buffer", [True, False])
+def test_reader_stream_copies_one_timestamp_while_later_updates_are_enqueued(hipmod, double_buffer):
+    """rudra_ps_weights_acquire / _release: a second stream is kept busy, then copies the weights of timestamp ts; in the
+    meantime the host enqueues the updates ts+1, ts+2 (and ts+3).  The launch that overwrites the buffer of ts must wait
+    for the reader: the copy equals the oracle's theta(ts) bit for bit, and so do the final weights."""
+    from paper_1509_04210_amd import binding as B
+    w = configs.C3(2).scaled(n_params=2_000_003, n_pushes=15 * 5)                 # c = 15, five updates
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, flags=B.FLAG_DOUBLE_BUFFER if double_buffer else 0, ring=15 * 5 + 1)
+    ora = OracleServer(w)
+    reader = torch.cuda.Stream()
+    big_a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")             # 1 GiB
+    big_b = torch.empty_like(big_a)
+    snapshot = torch.zeros(w.n_params, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    ts_l = [0] * w.n_learners
+    view_ts, theta_at_view, ticket = None, None, None
+    n_updates = 0
+    for i in range(len(learner)):
+        l, s = int(learner[i]), int(step[i])
+        _, _, applied = hip.push(l, s, ts_l[l])
+        ora.push(l, s, ts_l[l])
+        ts_l[l] = hip.pull_ts()
+        n_updates += applied
+        if applied and n_updates == 2:
+            _slow_work(reader, big_a, big_b, 40)                                  # the reader is busy for a while ...
+            ptr, view_ts, ticket = hip.ps.weights_acquire(reader.cuda_stream)
+            assert view_ts == 2 == ora.ps.ts
+            theta_at_view = ora.ps.theta.copy()
+            with torch.cuda.stream(reader):                                       # ... then copies the weights of timestamp 2
+                _copy_from_address(snapshot, ptr, w.n_params, reader)
+            assert hip.ps.weights_release(ticket, reader.cuda_stream) == B.OK
+    assert n_updates == 5
+    hip.ps.sync()
+    torch.cuda.synchronize()
+    assert np.array_equal(snapshot.cpu().numpy(), theta_at_view), "the reader saw weights of another timestamp"
+    assert np.array_equal(hip.weights().cpu().numpy(), ora.ps.theta)
+    st = hip.ps.stats()
+    assert st.n_weight_acquires == 1 and st.n_reader_waits == 1
+    # a release that comes after the overwriting launch was enqueued says so
+    _, _, late = hip.ps.weights_acquire(reader.cuda_stream)
+    assert hip.ps.weights_release(late, reader.cuda_stream) == B.OK               # nothing enqueued in between: fine
+    hip.close()
+
+
+def _copy_from_address(dst, src_ptr, n, stream):
+    """hipMemcpyAsync(dst, src_ptr, 4n bytes, device to device) on `stream`."""
+    import ctypes
+    rt = ctypes.CDLL("libamdhip64.so")
+    rt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    assert rt.hipMemcpyAsync(dst.data_ptr(), src_ptr, 4 * n, 3, stream.cuda_stream) == 0          # 3 = device to device
+
+
+def test_release_after_the_overwriting_launch_reports_it(hipmod):
+    from paper_1509_04210_amd import binding as B
+    w = _with(configs.C5.scaled(n_params=10_001, n_pushes=8), n_learners=2, n_split=2)      # c = 1: every push is an update
+    for flags, lifetime in ((0, 1), (B.FLAG_DOUBLE_BUFFER, 2)):
+        hip = hipmod.HipServer(w, flags=flags)
+        reader = torch.cuda.Stream()
+        _, ts, ticket = hip.ps.weights_acquire(reader.cuda_stream)
+        assert ts == 0
+        for k in range(lifetime):
+            assert hip.push(0, k, k)[2] == 1
+        assert hip.ps.weights_release(ticket, reader.cuda_stream) == B.ESTATE
+        assert hip.ps.weights_release(ticket + (1 << 20), reader.cuda_stream) == B.EINVAL     # a ticket from the future
+        # on the server's own stream no event is needed at all
+        _, _, ticket = hip.ps.weights_acquire(hip.sh)
+        assert hip.ps.weights_release(ticket, hip.sh) == B.OK
+        assert hip.ps.stats().n_reader_waits == 0
+        hip.close()

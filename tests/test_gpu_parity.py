@@ -18,7 +18,8 @@ TOL = 1e-5
 @pytest.fixture(scope="module")
 def hipmod():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_1509_04210_amd import binding, learners
+    from paper_1509_04210_amd import binding
+    from synth import learners
     binding.lib()            # fails loudly if the HIP library is not built
     gradgen.device_lib()
     return learners

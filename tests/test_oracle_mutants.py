@@ -46,6 +46,8 @@ MUTANTS = {
     "contributors_not_forgotten_after_the_step": ("  memset(o->seen, 0, o->cfg.n_learners);", ""),
     "caller_factor_ignored": ("double lr = (double)o->cfg.alpha0 * (double)o->cfg.lr_scale;", "double lr = (double)o->cfg.alpha0;"),
     "histogram_counts_timestamps": ("  int rc = count_staleness(o, sigma);", "  int rc = count_staleness(o, ts);"),
+    "gradient_norm_without_the_penalty": ("    gbar_sq += (double)gbar * (double)gbar;", "    gbar_sq += (double)(o->acc[k] * inv_c) * (double)(o->acc[k] * inv_c);"),
+    "hardsync_average_may_overshoot": ("  if (o->cfg.protocol == PROTO_HARDSYNC && (uint64_t)o->count + m > o->c) { o->n_rejected++; return OR_EHARDSYNC_DUP; }", ""),
     "adagrad_root_of_the_mean_square": ("      real denom = root + (real)o->cfg.adagrad_eps;", "      real denom = root / (real)sqrt((double)(o->n_updates + 1)) + (real)o->cfg.adagrad_eps;"),
 }
 

@@ -157,3 +157,19 @@ def test_aggregate_rejections():
     assert hard.push_aggregate(g, [0, 1])[0] == oracle.EHARDSYNC_STALE
     per = OraclePS(np.zeros(3, np.float32), 4, 1, oracle.SOFTSYNC, oracle.LR_PER_GRADIENT, max_aggregate=2)
     assert per.push_aggregate(g, [0, 0])[0] == oracle.EINVAL                      # a relayed average cannot be re-weighted
+
+
+def test_hardsync_step_under_a_tree_averages_exactly_lambda_gradients():
+    """Eq. 3: a hardsync step is the mean of one gradient from each of the lambda learners.  With relayed averages of up
+    to 3 gradients and lambda = 4, a second average of 3 would make 6: refused, nothing changes; the single gradient
+    that completes the four is taken and the step is theta - alpha * (3*a + b)/4, all dyadic, exact in binary32."""
+    ps = OraclePS(np.full(2, 8.0, np.float32), 4, 1, oracle.HARDSYNC, oracle.LR_CONST, alpha0=0.5, max_aggregate=3)
+    a, b = np.full(2, 2.0, np.float32), np.full(2, 10.0, np.float32)
+    assert ps.push_aggregate(a, [0, 0, 0])[0] == oracle.OK
+    rc, _ = ps.push_aggregate(a, [0, 0, 0])
+    assert rc == oracle.EHARDSYNC_DUP and (ps.pending, ps.ts, ps.n_rejected) == (3, 0, 1)
+    assert ps.push_aggregate(a, [0, 0])[0] == oracle.EHARDSYNC_DUP
+    rc, r = ps.push_aggregate(b, [0])
+    assert rc == oracle.OK and r.applied == 1 and ps.ts == 1
+    assert np.array_equal(ps.theta, np.full(2, 8.0 - 0.5 * (3 * 2.0 + 10.0) / 4, np.float32))      # 8 - 2 = 6
+    assert list(ps.clocks[0]) == [0, 0, 0, 0] and ps.n_pushes == 4

@@ -242,6 +242,34 @@ def test_norms():
     assert n == dict(theta_sq=4000.0, theta_inf=2.0, v_sq=4000.0, gbar_sq=4000.0)
 
 
+def test_norms_of_a_random_state_with_weight_penalty():
+    """Non-constant vectors, momentum and a weight penalty: the norms against sums written out here in numpy binary64
+    from the definitions.  ||gbar||^2 is taken of the averaged gradient AS THE RATE MULTIPLIES IT, i.e. with the
+    penalty term wd*theta (of the weights before the update) already added: that is the reading, and the variant
+    without the penalty differs by far more than the tolerance on this input."""
+    rng = _rng(21)
+    P, lam, wd, m, lr = 3001, 3, 0.25, 0.5, 0.125
+    w0 = rng.standard_normal(P).astype(np.float32)
+    ps = OraclePS(w0, lam, 1, oracle.HARDSYNC, oracle.LR_CONST, alpha0=lr, momentum=m, weight_decay=wd)
+    for step in range(3):
+        gs = (0.5 * rng.standard_normal((lam, P))).astype(np.float32)
+        if step == 2:                  # the latest update: its averaged gradient from the weights just before it
+            before = ps.theta.astype(np.float64)
+            mean = ((gs[0] + gs[1]) + gs[2]) * (np.float32(1) / np.float32(3))
+            gbar_with = mean.astype(np.float64) + wd * before
+            gbar_without = mean.astype(np.float64)
+        for l in range(lam):
+            assert ps.push(gs[l], step, l)[0] == 0
+    assert ps.ts == 3
+    n = ps.norms()
+    th, ve = ps.theta.astype(np.float64), ps.velocity.astype(np.float64)
+    assert n["theta_sq"] == pytest.approx(float(np.sum(th * th)), rel=1e-12)
+    assert n["v_sq"] == pytest.approx(float(np.sum(ve * ve)), rel=1e-12)
+    assert n["theta_inf"] == float(np.abs(th).max())
+    assert n["gbar_sq"] == pytest.approx(float(np.sum(gbar_with * gbar_with)), rel=1e-6)      # binary32 rounding of gbar itself
+    assert abs(n["gbar_sq"] - float(np.sum(gbar_without * gbar_without))) > 0.05 * n["gbar_sq"]
+
+
 # ---------------------------------------------------------------- AdaGrad (named for the ImageNet 1-softsync runs, Sec. 5.5)
 @pytest.mark.parametrize("wd", [0.0, 5e-4])
 def test_adagrad_equals_library_adagrad_on_the_averaged_gradient(wd):
