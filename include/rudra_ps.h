@@ -282,6 +282,29 @@ int rudra_ps_staleness_hist(rudra_ps_t* ps, uint64_t* out, uint64_t cap, uint64_
 int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out, uint32_t cap, uint32_t* n_out,
                           double* avg_sigma_out, float* lr_out);
 
+/* FOR CALLERS THAT CANNOT ALLOCATE (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): one sumGradients + applyUpdate with the fused norms, the update that the c-th rudra_ps_push_gradient
+ * triggers on a server with RUDRA_FLAG_STATS_NORMS, as a stateless call on the caller's own vectors.  It calls no
+ * hipMalloc / hipFree and no allocating routine: the per-workgroup norm slots that the server path keeps in
+ * hipMalloc'ed memory live in a fixed array in the library's device image (4 MiB per GPU, held until the process
+ * ends), and the slots are combined by a small second launch instead of on the host.
+ *   grads      HOST array of c DEVICE pointers (P floats each, 16-byte aligned, read once), summed in the order given
+ *   theta      DEVICE pointer, P floats, 16-byte aligned: weights, updated in place
+ *   state      DEVICE pointer, P floats, 16-byte aligned: velocity (momentum != 0) or AdaGrad's h, updated in place;
+ *              may be NULL for plain SGD
+ *   lr         the rate of this update (the caller's: this call keeps no timestamps and computes no staleness)
+ *   optimizer  enum rudra_optimizer; momentum, weight_decay, adagrad_eps as in rudra_ps_config_t
+ *   norms_out  DEVICE pointer to 4 doubles, 8-byte aligned: sum gbar^2, sum theta^2, sum state^2, max |theta| after
+ *              the update, valid once the work enqueued on `stream` has run
+ * Arithmetic and bits of theta and state are those of the server path.  Limits: c <= 64 and P <= 134 217 728
+ * (one norm slot per 1024-parameter tile); beyond either the call returns ERANGE and does nothing.
+ * All calls on one GPU share that GPU's slot array: calls whose device work can overlap (different streams without
+ * ordering between them) race on it and must be serialised by the caller; nothing in it needs clearing between calls.
+ * Errors: EINVAL (null / misaligned pointer, c = 0, P = 0, bad optimizer or device), ERANGE, EHIP. */
+int rudra_ps_apply_update_noalloc(const float* const* grads, uint32_t c, uint64_t n_params, float* theta, float* state,
+                                  float lr, float momentum, float weight_decay, int32_t optimizer, float adagrad_eps,
+                                  double* norms_out, int32_t device, void* stream);
+
 /* Learning-rate schedule hook (Sec. 4.2: alpha0 is divided by 10 after given epochs; epochs are the caller's). */
 int rudra_ps_set_lr(rudra_ps_t* ps, float alpha0);
 

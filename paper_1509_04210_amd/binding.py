@@ -81,6 +81,8 @@ def lib():
             "rudra_ps_set_lr": [vp, C.c_float],
             "rudra_ps_sync": [vp],
         }
+        sigs["rudra_ps_apply_update_noalloc"] = [C.POINTER(vp), u32, u64, vp, vp, C.c_float, C.c_float, C.c_float, i32, C.c_float,
+                                                 vp, i32, vp]
         for name, args in sigs.items():
             fn = getattr(L, name)
             fn.argtypes, fn.restype = args, C.c_int
@@ -105,6 +107,14 @@ def leaf_mean(grad_ptrs, n_params, out_ptr, device=0, stream=0):
     rc = lib().rudra_ps_leaf_mean(arr, len(grad_ptrs), n_params, out_ptr, device, stream or None)
     if rc != OK:
         raise RudraError(rc, "rudra_ps_leaf_mean")
+
+
+def apply_update_noalloc(grad_ptrs, n_params, theta_ptr, state_ptr, lr, momentum=0.0, weight_decay=0.0, optimizer=OPT_SGD,
+                         adagrad_eps=1e-8, norms_out_ptr=0, device=0, stream=0):
+    """rudra_ps_apply_update_noalloc: returns the C status."""
+    arr = (C.c_void_p * max(1, len(grad_ptrs)))(*grad_ptrs)
+    return lib().rudra_ps_apply_update_noalloc(arr, len(grad_ptrs), n_params, theta_ptr or None, state_ptr or None, lr, momentum,
+                                               weight_decay, optimizer, adagrad_eps, norms_out_ptr or None, device, stream or None)
 
 
 class ParameterServer:

@@ -248,6 +248,28 @@ __device__ __forceinline__ void block_reduce_norms(const Norms& n, double* parti
   }
 }
 
+// Combines the per-workgroup norm slots of one launch on the device: lane t adds the slots t, t + blockDim, ... in
+// that order, then the lanes' sums are added in lane order by lane 0 (fp64 throughout; the maximum likewise).  One
+// workgroup; the order is fixed by n_slots and blockDim alone, so the result is reproducible.  out[0..3] =
+// sum gbar^2, sum theta^2, sum v^2, max |theta|.
+__global__ void reduce_norm_slots_kernel(const double* slots, uint32_t n_slots, double* out) {
+  __shared__ double lds[256][kNumNorms];
+  double g = 0.0, t = 0.0, v = 0.0, m = 0.0;
+  for (uint32_t b = threadIdx.x; b < n_slots; b += blockDim.x) {
+    const double* s = slots + (uint64_t)b * kNumNorms;
+    g += s[0]; t += s[1]; v += s[2]; m = fmax(m, s[3]);
+  }
+  lds[threadIdx.x][0] = g; lds[threadIdx.x][1] = t; lds[threadIdx.x][2] = v; lds[threadIdx.x][3] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double dg = 0.0, dt = 0.0, dv = 0.0, dm = 0.0;
+    for (uint32_t l = 0; l < blockDim.x; ++l) {
+      dg += lds[l][0]; dt += lds[l][1]; dv += lds[l][2]; dm = fmax(dm, lds[l][3]);
+    }
+    out[0] = dg; out[1] = dt; out[2] = dv; out[3] = dm;
+  }
+}
+
 // Tiling: the vector of n4 = P/4 float4 positions is cut into tiles of blockDim*V positions;
 // within a tile lane t handles positions t, t+blockDim, ... so every load instruction of a
 // wave covers 1 KiB contiguous and a workgroup walks blockDim*V*16 contiguous bytes of each of

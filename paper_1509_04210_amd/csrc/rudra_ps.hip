@@ -24,6 +24,10 @@ using rudra::kMaxFused;
 using rudra::kNumNorms;
 using rudra::UpdateArgs;
 
+// Scratch of rudra_ps_apply_update_noalloc (see there).  Every GPU the library runs on holds its own copy at its own
+// address; host code reaches it only through the address hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) double g_noalloc_scratch[131072 * rudra::kNumNorms];
+
 namespace {
 
 constexpr uint32_t kDefaultBlock = 64;   // one wavefront per workgroup: finest dispatch granularity, measured fastest
@@ -67,6 +71,17 @@ class DeviceGuard {
   bool changed_ = false;
   hipError_t err_ = hipSuccess;
 };
+
+// rudra_ps_apply_update_noalloc: norm slots of its launch live in a file-scope device array instead of hipMalloc'ed
+// memory: one slot (kNumNorms doubles) per tile of kNoAllocBlock float4 positions.
+constexpr uint32_t kNoAllocBlock = 256;
+constexpr uint32_t kNoAllocSlots = 131072;  // 4 MiB of slots per GPU, held until the process ends
+constexpr uint64_t kNoAllocMaxParams = (uint64_t)kNoAllocSlots * kNoAllocBlock * 4;  // 134 217 728 parameters
+constexpr int kNoAllocMaxDevices = 64;
+
+static_assert(sizeof(g_noalloc_scratch) == (size_t)kNoAllocSlots * kNumNorms * sizeof(double), "scratch array and slot count disagree");
+std::mutex g_noalloc_mu;
+double* g_noalloc_slots[kNoAllocMaxDevices] = {};  // per device: address of its copy of g_noalloc_scratch
 
 struct Pending {
   const float* ptr;
@@ -934,6 +949,69 @@ int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params,
     if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
     have_head = true;
   }
+  return RUDRA_OK;
+}
+
+int rudra_ps_apply_update_noalloc(const float* const* grads, uint32_t c, uint64_t n_params, float* theta, float* state,
+                                  float lr, float momentum, float weight_decay, int32_t optimizer, float adagrad_eps,
+                                  double* norms_out, int32_t device, void* stream) {
+  if (!grads || !theta || !norms_out || c == 0 || n_params == 0) return RUDRA_EINVAL;
+  if (c > (uint32_t)kMaxFused || n_params > kNoAllocMaxParams) return RUDRA_ERANGE;  // beyond what the fixed scratch serves
+  if (optimizer != RUDRA_OPT_SGD && optimizer != RUDRA_OPT_ADAGRAD) return RUDRA_EINVAL;
+  if (optimizer == RUDRA_OPT_ADAGRAD && (momentum != 0.0f || !(adagrad_eps >= 0.0f))) return RUDRA_EINVAL;
+  if (!(lr == lr) || !(momentum == momentum) || !(weight_decay == weight_decay)) return RUDRA_EINVAL;
+  const int opt = optimizer == RUDRA_OPT_ADAGRAD ? rudra::kOptAdagrad : momentum != 0.0f ? rudra::kOptMomentum : rudra::kOptSgd;
+  if (opt != rudra::kOptSgd && !state) return RUDRA_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(theta) & 15u) || (reinterpret_cast<uintptr_t>(state) & 15u) ||
+      (reinterpret_cast<uintptr_t>(norms_out) & 7u))
+    return RUDRA_EINVAL;
+  for (uint32_t j = 0; j < c; ++j)
+    if (!grads[j] || (reinterpret_cast<uintptr_t>(grads[j]) & 15u)) return RUDRA_EINVAL;
+  if (device < 0 || device >= kNoAllocMaxDevices) return RUDRA_EINVAL;
+  DeviceGuard guard(device);
+  if (guard.error() != hipSuccess) { (void)hipGetLastError(); return RUDRA_EHIP; }
+
+  // The device address of this GPU's copy of the scratch array, looked up once per device with that device current.
+  // In host code the array's name is only a handle for this lookup: kernels and copies take `slots`, never the name.
+  double* slots = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_noalloc_mu);
+    if (!g_noalloc_slots[device]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return RUDRA_EHIP; }
+      g_noalloc_slots[device] = static_cast<double*>(p);
+    }
+    slots = g_noalloc_slots[device];
+  }
+
+  // one norm slot per tile of kNoAllocBlock float4 positions: no grid-stride, so the slot count is the tile count
+  const uint64_t n4 = n_params >> 2;
+  const uint64_t tiles = (n4 + kNoAllocBlock - 1) / kNoAllocBlock;
+  const uint32_t grid = (uint32_t)(tiles ? tiles : 1);  // <= kNoAllocSlots by the size check above
+  const uint32_t unroll = c > kDefaultUnroll ? 1u : kDefaultUnroll;
+  const LaunchShape shape = {grid, kNoAllocBlock, tiles,
+                             lds_for_occupancy(default_waves_per_cu(c, unroll, opt, n_params, kNoAllocBlock), kNoAllocBlock)};
+  GradSet gs;
+  std::memset(&gs, 0, sizeof(gs));
+  for (uint32_t j = 0; j < c; ++j) { gs.p[j] = grads[j]; gs.w[j] = 1.0f; }
+  UpdateArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.theta = theta;
+  a.theta_out = theta;
+  a.vel = state;
+  a.partials = slots;
+  a.n_params = n_params;
+  a.ntiles = tiles;
+  a.c = c;
+  a.inv_c = 1.0f / (float)c;  // Eq. 5
+  a.lr = lr;
+  a.momentum = momentum;
+  a.weight_decay = weight_decay;
+  a.adagrad_eps = adagrad_eps;
+  launch_apply(opt, weight_decay != 0.0f, false, true, unroll, 1, shape, (hipStream_t)stream, gs, a);
+  if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
+  hipLaunchKernelGGL(rudra::reduce_norm_slots_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, slots, grid, norms_out);
+  if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
   return RUDRA_OK;
 }
 

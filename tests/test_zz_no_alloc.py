@@ -1,0 +1,86 @@
+"""rudra_ps_apply_update_noalloc (the entry point for callers that cannot allocate) against the entry point it is a variant
+of: the update that the c-th rudra_ps_push_gradient triggers on a server with fused norms.  Same theta and state to the
+bit, same norms; two calls in a row, the second on a smaller input (the slot array keeps the first call's contents)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _server_path(B, P, grads, theta0, lr, momentum, wd, optimizer, eps):
+    """One hardsync step of c learners through create / push_gradient / pull / stats: the existing entry points."""
+    c = len(grads)
+    stream = torch.cuda.Stream()
+    ps = B.ParameterServer(P, c, theta0.data_ptr(), 1, B.HARDSYNC, B.LR_CONST, alpha0=lr, momentum=momentum, weight_decay=wd,
+                           optimizer=optimizer, adagrad_eps=eps, stream=stream.cuda_stream, flags=B.FLAG_STATS_NORMS)
+    for l, g in enumerate(grads):
+        rc, r = ps.push_gradient(g.data_ptr(), 0, l)
+        assert rc == 0
+    assert r.applied == 1 and np.float32(r.lr_used) == np.float32(lr)
+    theta, state = torch.empty(P, dtype=torch.float32, device="cuda"), None
+    torch.cuda.synchronize()
+    ps.pull_weights(theta.data_ptr())
+    if momentum != 0 or optimizer == B.OPT_ADAGRAD:
+        state = torch.empty(P, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        ps.pull_velocity(state.data_ptr())
+    ps.sync()
+    st = ps.stats()
+    assert st.norms_valid == 1
+    out = theta.cpu().numpy(), None if state is None else state.cpu().numpy(), (st.gbar_sq, st.theta_sq, st.v_sq, st.theta_inf)
+    ps.destroy()
+    return out
+
+
+def _case(B, seed, P, c, lr, momentum, wd, optimizer, eps, stream):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    theta0 = 0.01 * torch.randn(P, dtype=torch.float32, device="cuda", generator=g)
+    grads = [1e-3 * torch.randn(P, dtype=torch.float32, device="cuda", generator=g) for _ in range(c)]
+    torch.cuda.synchronize()
+    want_theta, want_state, want_norms = _server_path(B, P, grads, theta0, lr, momentum, wd, optimizer, eps)
+    theta = theta0.clone()
+    state = torch.zeros(P, dtype=torch.float32, device="cuda") if want_state is not None else None
+    norms = torch.full((4,), -1.0, dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+    rc = B.apply_update_noalloc([t.data_ptr() for t in grads], P, theta.data_ptr(), state.data_ptr() if state is not None else 0,
+                                lr, momentum, wd, optimizer, eps, norms.data_ptr(), 0, stream.cuda_stream)
+    assert rc == B.OK
+    stream.synchronize()
+    torch.cuda.synchronize()
+    assert np.array_equal(theta.cpu().numpy(), want_theta), "theta differs from the server path"
+    if state is not None:
+        assert np.array_equal(state.cpu().numpy(), want_state), "state differs from the server path"
+    got = norms.cpu().numpy()
+    for k in range(3):                                   # sums of the same binary32 terms, grouped differently: binary64 rounding only
+        assert abs(got[k] - want_norms[k]) <= 1e-9 * max(want_norms[k], 1e-300), (k, got[k], want_norms[k])
+    assert got[3] == want_norms[3]                       # a maximum: exact
+
+
+def test_noalloc_update_equals_the_server_path_twice_in_a_row_the_second_smaller():
+    assert torch.cuda.is_available()
+    from paper_1509_04210_amd import binding as B
+    B.lib()
+    stream = torch.cuda.Stream()
+    _case(B, 1, 300_003, 5, 0.05, 0.9, 5e-4, B.OPT_SGD, 0.0, stream)            # 293 tiles of 1024 parameters + a ragged tail
+    _case(B, 2, 70_001, 3, 0.01, 0.9, 0.0, B.OPT_SGD, 0.0, stream)              # smaller: 69 tiles; the other slots keep call 1's values
+    _case(B, 3, 4_099, 1, 0.1, 0.0, 0.0, B.OPT_SGD, 0.0, stream)                # plain SGD, no state vector
+    _case(B, 4, 20_002, 7, 0.05, 0.0, 5e-4, B.OPT_ADAGRAD, 1e-8, stream)
+    _case(B, 5, 2, 2, 0.05, 0.9, 0.0, B.OPT_SGD, 0.0, stream)                   # shorter than one float4: the scalar tail alone
+
+
+def test_noalloc_update_rejects_what_its_fixed_scratch_cannot_serve():
+    from paper_1509_04210_amd import binding as B
+    B.lib()
+    t = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    n = torch.zeros(4, dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+    p = t.data_ptr()
+    assert B.apply_update_noalloc([p] * 65, 1024, p, p, 0.1, norms_out_ptr=n.data_ptr()) == B.ERANGE          # more than 64 gradients
+    assert B.apply_update_noalloc([p], 134_217_729, p, p, 0.1, norms_out_ptr=n.data_ptr()) == B.ERANGE        # one past the maximum
+    assert B.apply_update_noalloc([], 1024, p, p, 0.1, norms_out_ptr=n.data_ptr()) == B.EINVAL
+    assert B.apply_update_noalloc([p], 1024, p + 4, p, 0.1, norms_out_ptr=n.data_ptr()) == B.EINVAL           # misaligned
+    assert B.apply_update_noalloc([p], 1024, p, 0, 0.1, momentum=0.9, norms_out_ptr=n.data_ptr()) == B.EINVAL  # momentum needs a state vector
+    assert B.apply_update_noalloc([p], 1024, p, p, 0.1, norms_out_ptr=0) == B.EINVAL
+    torch.cuda.synchronize()
+    assert float(t.abs().max()) == 0.0 and float(n.abs().max()) == 0.0          # nothing ran
