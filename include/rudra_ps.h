@@ -123,6 +123,10 @@ typedef struct {
   uint32_t launch_alternate; /* 1: successive updates walk the vector in opposite directions, so the theta/v lines
                                 written last are the first read next (memory-side cache reuse); 2: always forward;
                                 0 = library default (alternate) */
+  uint32_t launch_state_loads; /* which state vector the update kernel reads with non-temporal loads: 1 neither, 2 the
+                                velocity / AdaGrad sums, 3 the weights; 0 = library default (by c and by
+                                RUDRA_FLAG_DOUBLE_BUFFER, see the kernel header for the measurements).  Takes effect in the
+                                default launch shape (launch_vec 1, launch_unroll 1 or 4). */
 } rudra_ps_config_t;
 
 typedef struct {

@@ -64,6 +64,8 @@ struct BatchPlan {
 };
 
 enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second state vector, if any
+// which state vector is read with non-temporal loads (the other with ordinary ones); see "Cache policy" below
+enum : int { kStateLoadsCached = 0, kStateLoadsVelNt = 1, kStateLoadsThetaNt = 2 };
 
 // Cache policy (measured on MI355X at 72M parameters, c = 18 and c = 1):
 //   gradients   read once, never again: non-temporal loads (+4 %).
@@ -72,6 +74,13 @@ enum : int { kOptSgd = 0, kOptMomentum = 1, kOptAdagrad = 2 };  // which second 
 //               the vector in opposite directions (UpdateArgs::reverse): the lines written last by update i are the
 //               first read by update i+1 and part of them is still in the memory-side cache (+5 % at c = 18,
 //               +9 % at c = 1).
+//               One of the two state loads can be made non-temporal as well (template parameter NTLD; the host picks
+//               it by c and by whether there are two weight buffers, with the measurements, in state_load_policy).  With
+//               all 32 combinations of ordinary / non-temporal theta load, theta store, v load, v store and gradient load
+//               measured in one process on the same buffers, non-temporal stores and gradient loads always win and BOTH
+//               state loads non-temporal always lose (c = 1: 0.82 against 0.88-0.90 of 8 TB/s).  Marking only a region of
+//               theta / v as cacheable changes nothing (0 to 100 % of the vector tried): the reuse across updates happens in
+//               the memory-side cache, which does not see these hints.
 //   scope bits (sc0/sc1) make no difference (all 512 load/load/store policy combinations were tried).
 // Launch shape: one 64-lane wavefront per workgroup (6-8 % faster than 256-thread workgroups), and the host caps the
 // resident waves per CU by reserving unused LDS: what counts is the volume of loads in flight per CU and, at equal
@@ -90,7 +99,11 @@ __device__ __forceinline__ T load_grad_global(uint64_t p, uint64_t i) {
   return __builtin_nontemporal_load(reinterpret_cast<global_ptr>(p) + i);
 }
 __device__ __forceinline__ float load_grad1(const float* p, uint64_t k) { return __builtin_nontemporal_load(p + k); }
-__device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) { return p[iv]; }
+template <bool NT>
+__device__ __forceinline__ floatx4 load_state4(const floatx4* p, uint64_t iv) {
+  if (NT) return __builtin_nontemporal_load(p + iv);
+  else return p[iv];
+}
 __device__ __forceinline__ void store_state4(floatx4* p, uint64_t iv, floatx4 x) { __builtin_nontemporal_store(x, p + iv); }
 
 // Sum of the c gradients at V vector positions, in arrival order.  Loads are issued U
@@ -276,7 +289,7 @@ __global__ void reduce_norm_slots_kernel(const double* slots, uint32_t n_slots, 
 // the c+2 streams.  Workgroups take tiles blockIdx, blockIdx+gridDim, ... (grid-stride); the
 // host normally launches one workgroup per tile.  The last P%4 elements are done by the first
 // lanes of workgroup 0 with scalar accesses.
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int U, int V>
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int U, int V, int NTLD = kStateLoadsCached>
 __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
   const uint64_t n4 = a.n_params >> 2;
   const uint64_t tile = (uint64_t)blockDim.x * V;
@@ -296,8 +309,8 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       for (int v = 0; v < V; ++v) iv[v] = base + (uint64_t)v * blockDim.x;
 #pragma unroll
       for (int v = 0; v < V; ++v) {
-        th[v] = load_state4(theta4, iv[v]);
-        if (OPT != kOptSgd) ve[v] = load_state4(vel4, iv[v]);
+        th[v] = load_state4<NTLD == kStateLoadsThetaNt>(theta4, iv[v]);
+        if (OPT != kOptSgd) ve[v] = load_state4<NTLD == kStateLoadsVelNt>(vel4, iv[v]);
       }
       sum_gradients<WEIGHTED, U, V>(gs, a.c, iv, s);
 #pragma unroll
@@ -310,8 +323,8 @@ __global__ void apply_update_kernel(const GradSet gs, const UpdateArgs a) {
       for (int v = 0; v < V; ++v) {
         const uint64_t i1[1] = {base + (uint64_t)v * blockDim.x};
         if (i1[0] >= n4) break;
-        floatx4 th = load_state4(theta4, i1[0]), ve = {0.f, 0.f, 0.f, 0.f}, s[1];
-        if (OPT != kOptSgd) ve = load_state4(vel4, i1[0]);
+        floatx4 th = load_state4<NTLD == kStateLoadsThetaNt>(theta4, i1[0]), ve = {0.f, 0.f, 0.f, 0.f}, s[1];
+        if (OPT != kOptSgd) ve = load_state4<NTLD == kStateLoadsVelNt>(vel4, i1[0]);
         sum_gradients<WEIGHTED, U, 1>(gs, a.c, i1, s);
         update_vec4<OPT, DECAY, STATS>(s[0], th, ve, a, n);
         store_state4(theta_out4, i1[0], th);
@@ -401,7 +414,7 @@ __device__ __forceinline__ void batch_updates(const GradSet& gs, const BatchPlan
   consume(g, w_cur);
 }
 
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS>
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int NTLD = kStateLoadsCached>
 __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan, const UpdateArgs a) {
   typedef floatx4 T;
   const uint64_t npos = a.n_params >> 2;
@@ -414,8 +427,8 @@ __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan
     const uint64_t t = a.reverse ? ntiles - 1 - t0 : t0;
     const uint64_t i = t * blockDim.x + threadIdx.x;
     if (i >= npos) continue;
-    T th = theta[i], ve{};
-    if (OPT != kOptSgd) ve = vel[i];
+    T th = load_state4<NTLD == kStateLoadsThetaNt>(theta, i), ve{};
+    if (OPT != kOptSgd) ve = load_state4<NTLD == kStateLoadsVelNt>(vel, i);
     batch_updates<OPT, DECAY, WEIGHTED, STATS, T>(gs, plan, a, i, th, ve, n);
     __builtin_nontemporal_store(th, theta_out + i);
     if (OPT != kOptSgd) __builtin_nontemporal_store(ve, vel + i);

@@ -247,7 +247,18 @@ LaunchShape shape_for(const rudra_ps* ps) {
 
 // ---- kernel dispatch: runtime (optimizer, decay, weighted, stats, unroll, vec) -> template instance ----
 template <int OPT, bool WD, bool W, bool ST, int U>
-void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+void launch_apply_v(int ntld, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  // the state-load policies other than "both cached" exist for the default shapes only (one float4 per lane, 1 or 4 loads at a time)
+  if (vec == 1 && (U == 1 || U == 4) && ntld != rudra::kStateLoadsCached) {
+    if (ntld == rudra::kStateLoadsVelNt && OPT != rudra::kOptSgd) {
+      hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, (U == 1 || U == 4) ? U : 1, 1, rudra::kStateLoadsVelNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+      return;
+    }
+    if (ntld == rudra::kStateLoadsThetaNt) {
+      hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, (U == 1 || U == 4) ? U : 1, 1, rudra::kStateLoadsThetaNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a);
+      return;
+    }
+  }
   switch (vec) {
     case 1: hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, U, 1>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
     case 2: hipLaunchKernelGGL((rudra::apply_update_kernel<OPT, WD, W, ST, U, 2>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, a); break;
@@ -255,39 +266,66 @@ void launch_apply_v(uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& 
   }
 }
 template <int OPT, bool WD, bool W, bool ST>
-void launch_apply_u(uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+void launch_apply_u(int ntld, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (unroll) {
-    case 1: launch_apply_v<OPT, WD, W, ST, 1>(vec, s, st, gs, a); break;
-    case 2: launch_apply_v<OPT, WD, W, ST, 2>(vec, s, st, gs, a); break;
-    case 4: launch_apply_v<OPT, WD, W, ST, 4>(vec, s, st, gs, a); break;
-    default: launch_apply_v<OPT, WD, W, ST, 8>(vec, s, st, gs, a); break;
+    case 1: launch_apply_v<OPT, WD, W, ST, 1>(ntld, vec, s, st, gs, a); break;
+    case 2: launch_apply_v<OPT, WD, W, ST, 2>(ntld, vec, s, st, gs, a); break;
+    case 4: launch_apply_v<OPT, WD, W, ST, 4>(ntld, vec, s, st, gs, a); break;
+    default: launch_apply_v<OPT, WD, W, ST, 8>(ntld, vec, s, st, gs, a); break;
   }
 }
 template <int OPT, bool WD>
-void launch_apply_ws(bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
+void launch_apply_ws(bool weighted, bool stats, int ntld, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
                      const GradSet& gs, const UpdateArgs& a) {
   if (weighted) {
-    if (stats) launch_apply_u<OPT, WD, true, true>(unroll, vec, s, st, gs, a);
-    else launch_apply_u<OPT, WD, true, false>(unroll, vec, s, st, gs, a);
+    if (stats) launch_apply_u<OPT, WD, true, true>(ntld, unroll, vec, s, st, gs, a);
+    else launch_apply_u<OPT, WD, true, false>(ntld, unroll, vec, s, st, gs, a);
   } else {
-    if (stats) launch_apply_u<OPT, WD, false, true>(unroll, vec, s, st, gs, a);
-    else launch_apply_u<OPT, WD, false, false>(unroll, vec, s, st, gs, a);
+    if (stats) launch_apply_u<OPT, WD, false, true>(ntld, unroll, vec, s, st, gs, a);
+    else launch_apply_u<OPT, WD, false, false>(ntld, unroll, vec, s, st, gs, a);
   }
 }
 template <int OPT>
-void launch_apply_d(bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
+void launch_apply_d(bool decay, bool weighted, bool stats, int ntld, uint32_t unroll, uint32_t vec, LaunchShape s, hipStream_t st,
                     const GradSet& gs, const UpdateArgs& a) {
-  if (decay) launch_apply_ws<OPT, true>(weighted, stats, unroll, vec, s, st, gs, a);
-  else launch_apply_ws<OPT, false>(weighted, stats, unroll, vec, s, st, gs, a);
+  if (decay) launch_apply_ws<OPT, true>(weighted, stats, ntld, unroll, vec, s, st, gs, a);
+  else launch_apply_ws<OPT, false>(weighted, stats, ntld, unroll, vec, s, st, gs, a);
 }
-void launch_apply(int opt, bool decay, bool weighted, bool stats, uint32_t unroll, uint32_t vec, LaunchShape s,
+// ntld: which state vector is loaded non-temporally (rudra::kStateLoads...)
+void launch_apply(int opt, bool decay, bool weighted, bool stats, int ntld, uint32_t unroll, uint32_t vec, LaunchShape s,
                   hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   switch (opt) {
-    case rudra::kOptMomentum: launch_apply_d<rudra::kOptMomentum>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
-    case rudra::kOptAdagrad: launch_apply_d<rudra::kOptAdagrad>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
-    default: launch_apply_d<rudra::kOptSgd>(decay, weighted, stats, unroll, vec, s, st, gs, a); break;
+    case rudra::kOptMomentum: launch_apply_d<rudra::kOptMomentum>(decay, weighted, stats, ntld, unroll, vec, s, st, gs, a); break;
+    case rudra::kOptAdagrad: launch_apply_d<rudra::kOptAdagrad>(decay, weighted, stats, ntld, unroll, vec, s, st, gs, a); break;
+    default: launch_apply_d<rudra::kOptSgd>(decay, weighted, stats, ntld, unroll, vec, s, st, gs, a); break;
   }
 }
+
+// Which state vector the update kernels load non-temporally (the caller's launch_state_loads wins).  Measured at 72M
+// parameters with momentum or AdaGrad, all variants in one process on the same buffers, two machines (fraction of 8 TB/s,
+// neither / velocity / weights non-temporal):
+//   two weight buffers: the weights, always (the buffer read is dead once the update has run): c = 1 0.86 / 0.77-0.80 /
+//     0.89, c = 18 0.80 / 0.78 / 0.82: the double buffer then costs nothing against updating in place.
+//   in place, one update per launch: c = 1 0.887 / 0.905 / 0.903; c = 3 ... 14 +1.5 to +3.5 % for either (c = 5: 0.854 /
+//     0.887 / 0.886; c = 12: 0.826 / 0.839 / 0.839); c = 2 is the exception, on both machines (0.875 / 0.850 / 0.849);
+//     c >= 16 within 1 % either way (c = 18: 0.812 / 0.816 / 0.817; c = 30: 0.78 / 0.76-0.78 / 0.78).  The velocity is taken.
+//   plain SGD (no second state vector): ordinary loads (c = 1: 0.881 vs 0.864; c = 18: 0.821 vs 0.809).
+//   several updates per launch: up to about 40 gradients per launch the weights non-temporal is +1 to +6 % (varies
+//     with the machine, never below -1 %), beyond that ordinary loads are equal or 1 % better.
+int state_load_policy(const rudra_ps* ps, uint32_t n_grads) {
+  if (ps->cfg.launch_state_loads) return (int)ps->cfg.launch_state_loads - 1;
+  if (ps->double_buffer) return rudra::kStateLoadsThetaNt;
+  if (kernel_optimizer(ps->cfg) == rudra::kOptSgd) return rudra::kStateLoadsCached;
+  if (n_grads == 1 || (n_grads >= 3 && n_grads <= 14)) return rudra::kStateLoadsVelNt;
+  return rudra::kStateLoadsCached;
+}
+int batch_state_load_policy(const rudra_ps* ps, uint32_t n_grads) {
+  if (ps->cfg.launch_state_loads) return (int)ps->cfg.launch_state_loads - 1;
+  if (ps->double_buffer) return rudra::kStateLoadsThetaNt;
+  if (kernel_optimizer(ps->cfg) == rudra::kOptSgd) return rudra::kStateLoadsCached;
+  return n_grads <= 40 ? rudra::kStateLoadsThetaNt : rudra::kStateLoadsCached;
+}
+
 void launch_sum(bool weighted, LaunchShape s, uint32_t vec, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
   // the fold/accumulate path is not the measured one: a single shape (4 loads in flight)
   if (weighted) {
@@ -447,7 +485,7 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
   if (rc != RUDRA_OK) return rc;
   rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
-  launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, ps->unroll, ps->vec, s, ps->stream, gs, a);
+  launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, state_load_policy(ps, n), ps->unroll, ps->vec, s, ps->stream, gs, a);
   RUDRA_HIP(ps, hipGetLastError());
   rc = end_timed(ps, slot);
   if (rc != RUDRA_OK) return rc;
@@ -457,34 +495,39 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
 
 // ---- batched launches: several consecutive updates applied in registers (rudra_ps_push_batch) ----
 template <int OPT, bool WD, bool W, bool ST>
-void launch_batch_d(LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
-  hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+void launch_batch_d(int ntld, LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
+  if (ntld == rudra::kStateLoadsThetaNt)
+    hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsThetaNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  else if (ntld == rudra::kStateLoadsVelNt && OPT != rudra::kOptSgd)
+    hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsVelNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  else
+    hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
 }
 template <int OPT, bool WD>
-void launch_batch_ws(bool weighted, bool stats, LaunchShape s, hipStream_t st, const GradSet& gs,
+void launch_batch_ws(bool weighted, bool stats, int ntld, LaunchShape s, hipStream_t st, const GradSet& gs,
                      const BatchPlan& plan, const UpdateArgs& a) {
   if (weighted) {
-    if (stats) launch_batch_d<OPT, WD, true, true>(s, st, gs, plan, a);
-    else launch_batch_d<OPT, WD, true, false>(s, st, gs, plan, a);
+    if (stats) launch_batch_d<OPT, WD, true, true>(ntld, s, st, gs, plan, a);
+    else launch_batch_d<OPT, WD, true, false>(ntld, s, st, gs, plan, a);
   } else {
-    if (stats) launch_batch_d<OPT, WD, false, true>(s, st, gs, plan, a);
-    else launch_batch_d<OPT, WD, false, false>(s, st, gs, plan, a);
+    if (stats) launch_batch_d<OPT, WD, false, true>(ntld, s, st, gs, plan, a);
+    else launch_batch_d<OPT, WD, false, false>(ntld, s, st, gs, plan, a);
   }
 }
-void launch_batch(int opt, bool decay, bool weighted, bool stats, LaunchShape s, hipStream_t st,
+void launch_batch(int opt, bool decay, bool weighted, bool stats, int ntld, LaunchShape s, hipStream_t st,
                   const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
   switch (opt) {
     case rudra::kOptMomentum:
-      if (decay) launch_batch_ws<rudra::kOptMomentum, true>(weighted, stats, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptMomentum, false>(weighted, stats, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptMomentum, true>(weighted, stats, ntld, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptMomentum, false>(weighted, stats, ntld, s, st, gs, plan, a);
       break;
     case rudra::kOptAdagrad:
-      if (decay) launch_batch_ws<rudra::kOptAdagrad, true>(weighted, stats, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptAdagrad, false>(weighted, stats, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptAdagrad, true>(weighted, stats, ntld, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptAdagrad, false>(weighted, stats, ntld, s, st, gs, plan, a);
       break;
     default:
-      if (decay) launch_batch_ws<rudra::kOptSgd, true>(weighted, stats, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptSgd, false>(weighted, stats, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptSgd, true>(weighted, stats, ntld, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptSgd, false>(weighted, stats, ntld, s, st, gs, plan, a);
       break;
   }
 }
@@ -525,7 +568,7 @@ int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint3
   if (rc != RUDRA_OK) return rc;
   rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
-  launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, s, ps->stream, gs, plan, a);
+  launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, batch_state_load_policy(ps, n), s, ps->stream, gs, plan, a);
   RUDRA_HIP(ps, hipGetLastError());
   rc = end_timed(ps, slot);
   if (rc != RUDRA_OK) return rc;
@@ -609,7 +652,7 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->launch_unroll && c->launch_unroll != 1 && c->launch_unroll != 2 && c->launch_unroll != 4 && c->launch_unroll != 8)
     return RUDRA_EINVAL;
   if (c->launch_vec && c->launch_vec != 1 && c->launch_vec != 2 && c->launch_vec != 4) return RUDRA_EINVAL;
-  if (c->launch_alternate > 2) return RUDRA_EINVAL;
+  if (c->launch_alternate > 2 || c->launch_state_loads > 3) return RUDRA_EINVAL;
   if (c->max_aggregate > 1 && c->lr_mode == RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;  // a relayed average cannot be re-weighted
   if (c->max_aggregate > 4096) return RUDRA_EINVAL;
   if (c->launch_waves_per_cu && (c->launch_waves_per_cu < 2 || c->launch_waves_per_cu > 32)) return RUDRA_EINVAL;
@@ -1008,7 +1051,7 @@ int rudra_ps_apply_update_noalloc(const float* const* grads, uint32_t c, uint64_
   a.momentum = momentum;
   a.weight_decay = weight_decay;
   a.adagrad_eps = adagrad_eps;
-  launch_apply(opt, weight_decay != 0.0f, false, true, unroll, 1, shape, (hipStream_t)stream, gs, a);
+  launch_apply(opt, weight_decay != 0.0f, false, true, rudra::kStateLoadsCached, unroll, 1, shape, (hipStream_t)stream, gs, a);
   if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;
   hipLaunchKernelGGL(rudra::reduce_norm_slots_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, slots, grid, norms_out);
   if (hipGetLastError() != hipSuccess) return RUDRA_EHIP;

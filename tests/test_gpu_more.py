@@ -273,3 +273,22 @@ def test_release_after_the_overwriting_launch_reports_it(hipmod):
         assert hip.ps.weights_release(ticket, hip.sh) == B.OK
         assert hip.ps.stats().n_reader_waits == 0
         hip.close()
+
+
+# ---------------------------------------------------------------- which state vector is loaded non-temporally: never changes a bit
+@pytest.mark.parametrize("state_loads", [1, 2, 3])
+@pytest.mark.parametrize("double_buffer", [False, True])
+def test_state_load_policies_give_the_same_bits(hipmod, state_loads, double_buffer):
+    """launch_state_loads is a cache hint on the loads of theta / v: results do not depend on it, one by one or in runs."""
+    from paper_1509_04210_amd import binding as B
+    from tests.test_gpu_parity import _compare, _run_both, _run_both_batched
+    flags = B.FLAG_DOUBLE_BUFFER if double_buffer else 0
+    for base, P, n in ((configs.C5, 70_003, 60), (configs.C4, 33_331, 18 * 4), (configs.C4_ADAGRAD, 20_002, 18 * 3)):
+        w = base.scaled(n_params=P, n_pushes=n)
+        hip, ora = _run_both(hipmod, w, flags=flags, launch_state_loads=state_loads)
+        _compare(hip, ora, w)
+        hip.close()
+    w = configs.C5.scaled(n_params=70_003, n_pushes=90)
+    hip, ora = _run_both_batched(hipmod, w, [7, 20, 50], flags=flags, launch_state_loads=state_loads)
+    _compare(hip, ora, w)
+    hip.close()
