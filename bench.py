@@ -8,14 +8,18 @@ gradients per update, momentum 0.9, staleness-modulated rate): 18 pushGradient c
 (staleness, vector clock, rate on the host) and the fused sumGradients+applyUpdate kernel they trigger.
 Gradients are synthetic (seeded; 64 distinct 288 MB vectors pre-generated in HBM and cycled, far beyond
 the 256 MB Infinity Cache) and already resident when the timed region starts; the arrival order is the
-workload's seeded Exp(1) trace.  Prints ONE JSON line.
+workload's seeded Exp(1) trace.  After W warm-up steps the window of exactly K steps is timed --windows
+times (default 3) back to back; the headline is the median window.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import statistics
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -26,8 +30,9 @@ METRIC = "PS applyUpdates/sec and absorbed gradient GB/s (% HBM peak), 72M fp32 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
 
 # HBM bytes per applyUpdate launch measured with rocprofv3 --pmc (FETCH_SIZE, then WRITE_SIZE), each scaled by
-# the same counter's reading for a plain copy of known size (factors 1.99980 and 1.0); figures and commands in
-# profiles/apply_update_kernel_C4_C5_72M_hbm_traffic.md.  A measured constant, not recomputed at run time.
+# the same counter's reading for a plain copy of known size; figures, commands and the commit they were taken at are in
+# profiles/apply_update_kernel_C4_C5_72M_hbm_traffic.md.  Measured constants, not recomputed at run time; a test
+# (tests/test_bench_constants.py) fails when one of them is more than 1 % away from the algorithmic bytes of its launch.
 MEASURED_TRAFFIC_BYTES = {"C4": 6.3355e9, "C5": 1.43995e9}
 MEASURED_TRAFFIC_BYTES_BATCH8 = {"C5": 3.4558e9}   # same files: C5 with 8 messages per call
 
@@ -38,15 +43,17 @@ def algorithmic_bytes_per_update(w) -> int:
     return w.n_params * (4 * w.c + 8 + (8 if second_state else 0))
 
 
-def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, **launch):
-    """Replays (warmup+steps)*c pushes of the workload's arrival trace; returns timings of the last `steps` updates.
-    batch > 1: the messages are handed over `batch` at a time (rudra_ps_push_batch; a learner pulls after the call
-    that held its push), so consecutive updates share a launch."""
+def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, windows=3, **launch):
+    """Replays (warmup + windows*steps)*c pushes of the workload's arrival trace; after the warm-up, `windows` windows of
+    exactly `steps` updates are timed back to back (host wall clock from the first push of the window to stream idle, and
+    HIP events on the server's stream around the window's launches); medians and minima over the windows are returned.
+    batch > 1: the messages are handed over `batch` at a time (rudra_ps_push_batch; a learner pulls after the call that
+    held its push), so consecutive updates share a launch."""
     import torch
     from synth.learners import HipServer
 
     c = w.c
-    learner, step = w.arrival_trace((warmup + steps) * c)
+    learner, step = w.arrival_trace((warmup + windows * steps) * c)
     hip = HipServer(w, flags=flags, pregenerated=max(ring, c + 1), **launch)
     ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
     nbuf = len(bufs)
@@ -86,20 +93,27 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, **launch):
     run_range(0, warmup * c)
     ps.sync()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    launches_before = 0 if flags & 8 else ps.stats().n_apply_launches     # (with the kernel timer on, stats() would wait)
-    e0.record(hip.stream)
-    t0 = time.perf_counter()
-    run_range(warmup * c, (warmup + steps) * c)
-    e1.record(hip.stream)
-    ps.sync()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ev_ms = e0.elapsed_time(e1)
+    timer_on = bool(flags & 8)              # (with the kernel timer on, stats() would wait for the launches)
+    wall, ev_ms, launches = [], [], []
+    for k in range(windows):
+        lo = (warmup + k * steps) * c
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        before = 0 if timer_on else ps.stats().n_apply_launches
+        e0.record(hip.stream)
+        t0 = time.perf_counter()
+        run_range(lo, lo + steps * c)
+        e1.record(hip.stream)
+        ps.sync()
+        torch.cuda.synchronize()
+        wall.append(time.perf_counter() - t0)
+        ev_ms.append(e0.elapsed_time(e1))
+        launches.append(0 if timer_on else ps.stats().n_apply_launches - before)
     st = ps.stats()
-    assert st.n_updates == warmup + steps, (st.n_updates, warmup + steps)
-    out = dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * c, sigma_mean=st.sigma_mean,
-               kernel_ms=st.kernel_ms, kernel_launches=st.kernel_launches, timed_launches=st.n_apply_launches - launches_before)
+    assert st.n_updates == warmup + windows * steps, (st.n_updates, warmup, windows, steps)
+    n_launches = sum(launches) / len(launches)          # (batched hand-over: windows can differ by one launch)
+    out = dict(wall_s=statistics.median(wall), wall_s_min=min(wall), wall_windows=wall, event_ms=statistics.median(ev_ms),
+               event_ms_min=min(ev_ms), updates=steps, pushes=steps * c, sigma_mean=st.sigma_mean, kernel_ms=st.kernel_ms,
+               kernel_launches=st.kernel_launches, timed_launches=n_launches, windows=windows)
     # sanity: the state is finite and moved
     chk = hip.weights()
     out["theta_absmax"] = float(chk.abs().max())
@@ -153,30 +167,89 @@ def run_gpu_tree(w, fan_in, steps, warmup, ring=64):
     return dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * w.c)
 
 
-def run_copy_ceiling(n_params, reps=20):
-    """What a plain device-to-device copy of one parameter vector reaches on this machine (read + write bytes over time):
-    context for the roofline fraction, not a target."""
+def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
+    """A workload with the pullWeights traffic of its learners: after every applyUpdate each of the lambda learners fetches
+    the new weights (a device copy of the vector each).  overlap = False: rudra_ps_pull_weights, i.e. the copies queue on
+    the server's stream between the updates.  overlap = True: two weight buffers (RUDRA_FLAG_DOUBLE_BUFFER), the copies run
+    on reader streams from the buffer rudra_ps_weights_acquire hands out, concurrently with the next update, and
+    rudra_ps_weights_release makes the update after that one wait for them (Sec. 3.3: computation and communication
+    buffers with a pointer swap)."""
     import torch
-    src = torch.empty(n_params, dtype=torch.float32, device="cuda").normal_()
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        dst.copy_(src)
+    from paper_1509_04210_amd import binding as B
+    from synth.learners import HipServer
+
+    c, lam, P = w.c, w.n_learners, w.n_params
+    learner, _ = w.arrival_trace((warmup + steps) * c)
+    learner = [int(x) for x in learner]
+    hip = HipServer(w, flags=B.FLAG_DOUBLE_BUFFER if overlap else 0, pregenerated=max(ring, c + 1))
+    ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
+    dsts = [torch.empty(P, dtype=torch.float32, device=hip.dev) for _ in range(4)]      # where the learners' copies land
+    readers = [torch.cuda.Stream(device=hip.dev) for _ in range(n_reader_streams)]
+    rt = ctypes.CDLL("libamdhip64.so")
+    rt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        dst.copy_(src)
-    e1.record()
+    learner_ts = [0] * lam
+    n_copies = 0
+
+    def all_learners_pull():
+        nonlocal n_copies
+        if not overlap:
+            for l in range(lam):
+                ps.pull_weights(dsts[l % len(dsts)].data_ptr())
+                n_copies += 1
+            return
+        for r, rs in enumerate(readers):
+            ptr, _, ticket = ps.weights_acquire(rs.cuda_stream)
+            for l in range(r, lam, len(readers)):
+                if rt.hipMemcpyAsync(dsts[l % len(dsts)].data_ptr(), ptr, 4 * P, 3, rs.cuda_stream) != 0:     # 3 = device to device
+                    raise RuntimeError("hipMemcpyAsync failed")
+                n_copies += 1
+            if ps.weights_release(ticket, rs.cuda_stream) != B.OK:
+                raise RuntimeError("weights_release came too late")
+
+    def run_range(lo, hi):
+        for i in range(lo, hi):
+            l = learner[i]
+            rc, res = ps.push_gradient(bufs[i % len(bufs)], learner_ts[l], l)
+            if rc != 0:
+                raise RuntimeError(f"push {i} rejected: {rc}")
+            learner_ts[l] = res.ts_after
+            if res.applied:
+                all_learners_pull()
+
+    run_range(0, warmup * c)
+    ps.sync()
     torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
-    del src, dst
+    n_copies = 0
+    t0 = time.perf_counter()
+    run_range(warmup * c, (warmup + steps) * c)
+    ps.sync()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    st = ps.stats()
+    hip.close()
+    del dsts
     torch.cuda.empty_cache()
-    return 8 * n_params / (ms * 1e-3) / 1e9
+    return dict(wall_s=wall, updates=steps, copies=n_copies, reader_waits=st.n_reader_waits)
+
+
+def run_stream_ceilings(n, ptrs, sink_ptr, stream=0):
+    """What plain streaming kernels reach on this machine over buffers of the same size (the harness's own kernels, synth/csrc/
+    streambench.hip; not the product): read-only passes over 3 and 20 vectors (the stream counts of the c = 1 and c = 18
+    launches) and a copy; best of two disjoint buffer sets each."""
+    from synth import streambench
+    out = {}
+    for k in (3, 20):
+        out[f"read_{k}_streams"] = max(streambench.read_gbps(ptrs[j * k:(j + 1) * k], n, sink_ptr, reps=10, stream=stream) for j in range(2))
+    out["copy"] = max(streambench.copy_gbps(ptrs[2 * j], ptrs[2 * j + 1], n, reps=20, stream=stream) for j in range(2))
+    return out
 
 
 def run_cpu_oracle(w, n_updates=30, n_distinct=3):
-    """The CPU oracle as it stands, single thread, on the full-size vector: `n_updates` applyUpdates of the same
-    workload.  Gradient materialisation is excluded from the timing (as on the GPU)."""
+    """The CPU oracle as it stands on the full-size vector, `n_updates` applyUpdates of the same workload, twice: on one
+    thread, and with the element range cut into one contiguous slice per host core, each slice replayed by its own
+    instance of the same oracle on its own thread (the update is elementwise, so every element sees the same operations
+    in the same order: the results are asserted bit-identical).  Gradient materialisation is excluded (as on the GPU)."""
     import numpy as np
     import torch
     from oracle.adapter import LR_MODE, PROTOCOL
@@ -194,18 +267,54 @@ def run_cpu_oracle(w, n_updates=30, n_distinct=3):
 
     init = device_vector(w.init_key(), w.init_std, 0)
     grads = [device_vector(w.grad_key(l, 0), w.grad_std, w.tail_per) for l in range(n_distinct)]
-    ps = OraclePS(init, w.n_learners, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode], w.alpha0, w.lr_scale,
-                  w.momentum, w.weight_decay, w.c_override)
+    del buf
     learner, _ = w.arrival_trace(n_updates * w.c)
-    learner_ts = [0] * w.n_learners
+    learner = [int(x) for x in learner]
+
+    def replay(lo, hi):
+        ps = OraclePS(init[lo:hi], w.n_learners, w.n_split, PROTOCOL[w.protocol], LR_MODE[w.lr_mode], w.alpha0, w.lr_scale,
+                      w.momentum, w.weight_decay, w.c_override)
+        sl = [g[lo:hi] for g in grads]
+        learner_ts = [0] * w.n_learners
+        t0 = time.perf_counter()
+        for i, l in enumerate(learner):
+            rc, res = ps.push(sl[i % n_distinct], learner_ts[l], l)
+            assert rc == 0
+            learner_ts[l] = res.ts_after
+        dt = time.perf_counter() - t0
+        assert ps.ts == n_updates
+        return ps, dt
+
+    ps1, dt1 = replay(0, P)
+    theta1 = ps1.theta
+    ps1.close()
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))       # a one-GPU machine's share of host cores is 16
+    bounds = [P * k // cores for k in range(cores + 1)]
+    parts = [None] * cores
+
+    def work(k):
+        parts[k] = replay(bounds[k], bounds[k + 1])
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(cores)]
     t0 = time.perf_counter()
-    for i, l in enumerate(learner):
-        rc, res = ps.push(grads[i % n_distinct], learner_ts[int(l)], int(l))
-        assert rc == 0
-        learner_ts[int(l)] = res.ts_after
-    dt = time.perf_counter() - t0
-    assert ps.ts == n_updates
-    return dict(value=n_updates / dt, seconds=dt, updates=n_updates)
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    dtn = time.perf_counter() - t0
+    assert all(p is not None for p in parts)
+    for k, (ps, _) in enumerate(parts):
+        assert np.array_equal(ps.theta, theta1[bounds[k]:bounds[k + 1]]), "sliced oracle differs from the single-thread oracle"
+        ps.close()
+    return dict(updates=n_updates, single_value=n_updates / dt1, single_seconds=dt1, cores=cores, value=n_updates / dtn, seconds=dtn)
+
+
+def _extra_entry(r, bytes_per_launch, n_params):
+    ms = r["event_ms"] / r["timed_launches"]
+    return {"applyUpdates_per_s": r["updates"] / r["wall_s"], "absorbed_gradient_GBps": r["pushes"] * 4 * n_params / r["wall_s"] / 1e9,
+            "avg_launch_ms": ms, "updates_per_launch": r["updates"] / r["timed_launches"], "bytes_per_launch": bytes_per_launch,
+            "achieved_GBps": bytes_per_launch / (ms * 1e-3) / 1e9, "frac": bytes_per_launch / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "mean_staleness": r["sigma_mean"], "timed_windows": r["windows"]}
 
 
 def main():
@@ -213,6 +322,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--windows", type=int, default=3, help="how many times the window of --steps updates is timed (the median is the headline)")
     ap.add_argument("--workload", default="C4",
                     help="C4 (default, the headline) or any other key of synth.configs.ALL; the small workloads (C1-C3) are "
                          "cache-resident and launch-bound: read their applyUpdates/s, not their roofline fraction")
@@ -221,14 +331,19 @@ def main():
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--vec", type=int, default=0)
     ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--learners", type=int, default=0, help="run the workload's recipe with this many learners (under 1-softsync c = lambda)")
     ap.add_argument("--double-buffer", action="store_true", help="run the server with RUDRA_FLAG_DOUBLE_BUFFER")
     ap.add_argument("--batch", type=int, default=1,
                     help="hand the messages over this many at a time (rudra_ps_push_batch): consecutive updates share a launch; "
                          "the headline is measured with 1 (every update its own launch)")
     ap.add_argument("--waves", type=int, default=0, help="launch_waves_per_cu")
+    ap.add_argument("--state-loads", type=int, default=0, help="launch_state_loads")
     ap.add_argument("--params", type=int, default=0, help="run the workload's recipe at another vector length (size sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel event pass and the second workload")
+    ap.add_argument("--no-extra", action="store_true", help="skip the bandwidth probes, the per-kernel event pass and the other workloads")
+    ap.add_argument("--probes-only", action="store_true",
+                    help="run only the harness's streaming probes (read-only over 3 and 20 vectors, copy) and print their GB/s: "
+                         "the reference launches for counter runs")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also run this many plain device copies of P floats (known size: 4P bytes read, 4P written) so that "
                          "a rocprofv3 --pmc run of this command has a reference reading for FETCH_SIZE / WRITE_SIZE")
@@ -240,26 +355,37 @@ def main():
 
     import torch
     import __graft_entry__
-    __graft_entry__.ensure_built()          # loads what is built; builds only on a fresh checkout
+    __graft_entry__.ensure_built()          # loads what is built; rebuilds only what is missing or older than its sources
+    from dataclasses import replace
     from paper_1509_04210_amd import binding as B
     from synth import configs
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
+    if args.probes_only:
+        n = configs.ALL[args.workload].n_params // 4 * 4
+        pool = [torch.empty(n, dtype=torch.float32, device="cuda").normal_(std=1e-4) for _ in range(40)]
+        sink = torch.zeros(1024, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        print(json.dumps({"stream_probes_GBps": run_stream_ceilings(n, [t.data_ptr() for t in pool], sink.data_ptr()), "n_floats": n}))
+        return
     launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid,
-                  launch_waves_per_cu=args.waves)
+                  launch_waves_per_cu=args.waves, launch_state_loads=args.state_loads)
     w = configs.ALL[args.workload]
     if args.params:
         w = w.scaled(n_params=args.params, name=f"{w.name}@{args.params}")
+    if args.learners:
+        w = replace(w, name=f"{w.name}-{args.learners}-learners", n_learners=args.learners)
     base_flags = B.FLAG_DOUBLE_BUFFER if args.double_buffer else 0
-    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, batch=args.batch, **launch)
+    r = run_gpu(w, args.steps, args.warmup, ring=args.ring, flags=base_flags, batch=args.batch, windows=args.windows, **launch)
     bytes_upd = algorithmic_bytes_per_update(w)
     if args.batch > 1:      # per launch: every gradient of its updates once, theta (and the second state vector) once
-        bytes_upd = (r["pushes"] * 4 * w.n_params + r["timed_launches"] * (bytes_upd - 4 * w.c * w.n_params)) // r["timed_launches"]
+        bytes_upd = int((r["pushes"] * 4 * w.n_params + r["timed_launches"] * (bytes_upd - 4 * w.c * w.n_params)) / r["timed_launches"])
     ups = r["updates"] / r["wall_s"]
     kernel_ms = r["event_ms"] / r["timed_launches"]     # the timed region is back-to-back applyUpdate launches only
     achieved = bytes_upd / (kernel_ms * 1e-3) / 1e9
-    traffic = (None if args.params else MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else
+    plain = not (args.params or args.learners or args.double_buffer)
+    traffic = (None if not plain else MEASURED_TRAFFIC_BYTES.get(args.workload) if args.batch == 1 else
                MEASURED_TRAFFIC_BYTES_BATCH8.get(args.workload) if args.batch == 8 else None)
     line = {
         "metric": METRIC, "value": ups, "unit": "applyUpdates/s", "n_gpus": 1, "steps": args.steps,
@@ -269,13 +395,17 @@ def main():
                                f"momentum={w.momentum}, wd={w.weight_decay}, lr=alpha0/max(1,<sigma>), "
                                f"ring of {max(args.ring, w.c + 1)} pre-generated gradients",
                    "pushes_per_step": w.c, "launch": {k: v for k, v in launch.items() if v},
-                   "double_buffer": bool(args.double_buffer), "messages_per_call": args.batch},
+                   "double_buffer": bool(args.double_buffer), "messages_per_call": args.batch,
+                   "timed_windows": args.windows, "headline": "median of the timed windows of `steps` steps each"},
+        "ms_per_step_min": 1e3 * r["wall_s_min"] / r["updates"],
+        "ms_per_step_windows": [1e3 * x / r["updates"] for x in r["wall_windows"]],
         "absorbed_gradient_GBps": r["pushes"] * 4 * w.n_params / r["wall_s"] / 1e9,
         "pushes_per_s": r["pushes"] / r["wall_s"],
         "mean_staleness": r["sigma_mean"],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "apply_update_kernel" if args.batch == 1 else "apply_update_batch_kernel", "bytes_per_launch": bytes_upd, "avg_launch_ms": kernel_ms},
+                     "kernel": "apply_update_kernel" if args.batch == 1 else "apply_update_batch_kernel", "bytes_per_launch": bytes_upd,
+                     "avg_launch_ms": kernel_ms, "avg_launch_ms_min": r["event_ms_min"] / r["timed_launches"]},
     }
     if args.calibration_copies:
         src = torch.empty(w.n_params, dtype=torch.float32, device="cuda").normal_()
@@ -285,9 +415,18 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_extra:
-        line["roofline"]["device_copy_GBps"] = run_copy_ceiling(w.n_params)
+        # what plain streaming kernels reach over buffers of the same size on this machine (harness kernels, not the product)
+        n = w.n_params // 4 * 4
+        pool = [torch.empty(n, dtype=torch.float32, device="cuda").normal_(std=1e-4) for _ in range(40)]
+        sink = torch.zeros(1024, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        ceil = run_stream_ceilings(n, [t.data_ptr() for t in pool], sink.data_ptr())
+        line["roofline"]["stream_read_GBps"] = {"3_streams": ceil["read_3_streams"], "20_streams": ceil["read_20_streams"]}
+        line["roofline"]["stream_copy_GBps"] = ceil["copy"]
+        del pool, sink
+        torch.cuda.empty_cache()
         # per-launch HIP events around every applyUpdate (library flag), same workload
-        rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=base_flags | B.FLAG_TIME_KERNELS, **launch)
+        rt = run_gpu(w, min(args.steps, 100), args.warmup, ring=args.ring, flags=base_flags | B.FLAG_TIME_KERNELS, windows=1, **launch)
         k_ms = rt["kernel_ms"] / max(1, rt["kernel_launches"])
         line["roofline"]["per_launch_event_ms"] = k_ms
         line["roofline"]["per_launch_event_GBps"] = bytes_upd / (k_ms * 1e-3) / 1e9
@@ -296,34 +435,28 @@ def main():
         line["extra"] = {}
         for other in ([configs.C5] if args.workload == "C4" else [configs.C4]) + [configs.C4_ADAGRAD]:
             ro = run_gpu(other, 1000 if other.c == 1 else 200, 10, ring=args.ring, flags=base_flags, **launch)
-            bo = algorithmic_bytes_per_update(other)
-            o_ms = ro["event_ms"] / ro["updates"]
-            line["extra"][other.name] = {
-                "applyUpdates_per_s": ro["updates"] / ro["wall_s"],
-                "absorbed_gradient_GBps": ro["pushes"] * 4 * other.n_params / ro["wall_s"] / 1e9,
-                "avg_launch_ms": o_ms, "achieved_GBps": bo / (o_ms * 1e-3) / 1e9,
-                "frac": bo / (o_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "bytes_per_launch": bo,
-                "mean_staleness": ro["sigma_mean"]}
+            line["extra"][other.name] = _extra_entry(ro, algorithmic_bytes_per_update(other), other.n_params)
+        if not args.double_buffer:      # both again with two weight buffers (Sec. 3.3 pointer swap): same bytes per launch
+            for other in (configs.C4, configs.C5):
+                ro = run_gpu(other, 1000 if other.c == 1 else 200, 10, ring=args.ring, flags=B.FLAG_DOUBLE_BUFFER, **launch)
+                line["extra"][other.name + "-double-buffer"] = _extra_entry(ro, algorithmic_bytes_per_update(other), other.n_params)
     if not args.no_extra and args.batch == 1:
-        # C5 again with the messages handed over 8 at a time (rudra_ps_push_batch): 8 updates per launch, theta and v
-        # touched once per launch: P*(4*8 + 16) bytes instead of 8*P*20
-        rb = run_gpu(configs.C5, 1024, 64, ring=max(args.ring, 64), flags=base_flags, batch=8, **launch)
-        bb = (rb["pushes"] * 4 + rb["timed_launches"] * 16) * configs.C5.n_params // rb["timed_launches"]
-        b_ms = rb["event_ms"] / rb["timed_launches"]
-        line["extra"]["C5-8-messages-per-call"] = {
-            "applyUpdates_per_s": rb["updates"] / rb["wall_s"], "absorbed_gradient_GBps": rb["pushes"] * 4 * configs.C5.n_params / rb["wall_s"] / 1e9,
-            "avg_launch_ms": b_ms, "updates_per_launch": rb["updates"] / rb["timed_launches"], "bytes_per_launch": bb,
-            "achieved_GBps": bb / (b_ms * 1e-3) / 1e9, "frac": bb / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "kernel": "apply_update_batch_kernel"}
+        # C5 again with the messages handed over 8, 16 and 64 at a time (rudra_ps_push_batch): k updates per launch, theta
+        # and v touched once per launch: P*(4k + 16) bytes instead of k*P*20
+        for k in (8, 16, 64):
+            rb = run_gpu(configs.C5, 1024 if k < 64 else 1280, 64, ring=max(args.ring, k + 2), flags=base_flags, batch=k, **launch)
+            bb = int((rb["pushes"] * 4 + rb["timed_launches"] * 16) * configs.C5.n_params / rb["timed_launches"])
+            e = _extra_entry(rb, bb, configs.C5.n_params)
+            e["kernel"] = "apply_update_batch_kernel"
+            line["extra"][f"C5-{k}-messages-per-call"] = e
     if not args.no_extra:
-        # 54 learners, 1-softsync (the shape of the paper's Rudra-adv ImageNet run, Table 4): flat, and as a tree with nodes of 3
-        from dataclasses import replace
+        # more learners, 1-softsync, flat: c = 30 (the CIFAR10 runs' learner count, at ImageNet size) and c = 54 (the shape of
+        # the paper's Rudra-adv ImageNet run, Table 4); c = 54 also as a tree with nodes of 3
+        for lam in (30, 54):
+            wl = replace(configs.C4, name=f"C4-{lam}-learners-flat", n_learners=lam)
+            rf = run_gpu(wl, 60, 5, ring=max(args.ring, lam + 10), flags=base_flags, **launch)
+            line["extra"][wl.name] = _extra_entry(rf, algorithmic_bytes_per_update(wl), wl.n_params)
         w54 = replace(configs.C4, name="C4-54-learners-flat", n_learners=54)
-        rf = run_gpu(w54, 60, 5, ring=args.ring, flags=base_flags, **launch)
-        bf = algorithmic_bytes_per_update(w54)
-        line["extra"][w54.name] = {"applyUpdates_per_s": rf["updates"] / rf["wall_s"], "avg_launch_ms": rf["event_ms"] / rf["updates"],
-                                   "absorbed_gradient_GBps": rf["pushes"] * 4 * w54.n_params / rf["wall_s"] / 1e9,
-                                   "achieved_GBps": bf / (rf["event_ms"] / rf["updates"] * 1e-3) / 1e9, "bytes_per_launch": bf}
         rt3 = run_gpu_tree(w54, 3, 60, 5, ring=args.ring)
         # per update: 18 node launches of (3 reads + 1 write) and the root launch over 18 relayed averages + theta, v
         bt = w54.n_params * ((w54.c // 3) * 16 + 4 * (w54.c // 3) + 16)
@@ -332,12 +465,25 @@ def main():
             "absorbed_gradient_GBps": rt3["pushes"] * 4 * w54.n_params / rt3["wall_s"] / 1e9,
             "achieved_GBps": bt / (rt3["event_ms"] / rt3["updates"] * 1e-3) / 1e9, "bytes_per_update": bt,
             "launches_per_update": w54.c // 3 + 1}
+        # C4 with its learners' pullWeights traffic (18 copies of the weights per update): queued on the server's stream,
+        # or overlapped with the next update from the second weight buffer (Sec. 3.3)
+        pulls = {}
+        for name, overlap in (("serialized_on_the_server_stream", False), ("overlapped_from_the_second_buffer", True)):
+            rp = run_gpu_pulls(configs.C4, 40, 4, overlap)
+            moved = rp["updates"] * algorithmic_bytes_per_update(configs.C4) + rp["copies"] * 8 * configs.C4.n_params
+            pulls[name] = {"applyUpdates_per_s": rp["updates"] / rp["wall_s"], "ms_per_update": 1e3 * rp["wall_s"] / rp["updates"],
+                           "weight_copies_per_update": rp["copies"] / rp["updates"], "HBM_GBps_updates_plus_copies": moved / rp["wall_s"] / 1e9,
+                           "launches_made_to_wait_for_readers": rp["reader_waits"]}
+        line["extra"]["C4-with-18-weight-pulls-per-update"] = pulls
     if not args.no_cpu_baseline:
         cb = run_cpu_oracle(w)
-        line["cpu_baseline"] = {"value": cb["value"], "unit": "applyUpdates/s", "cores": 1, "kind": "oracle",
+        line["cpu_baseline"] = {"value": cb["value"], "unit": "applyUpdates/s", "cores": cb["cores"], "kind": "oracle",
                                 "sample": f"{cb['updates']} applyUpdates ({cb['updates'] * w.c} pushes) of the same workload on the full "
-                                          f"{w.n_params}-element vector, single thread, {cb['seconds']:.1f} s, gradients pre-materialised",
-                                "GBps": cb["value"] * bytes_upd / 1e9}
+                                          f"{w.n_params}-element vector, gradients pre-materialised; the element range cut into "
+                                          f"{cb['cores']} slices, one instance of the oracle and one thread per slice, {cb['seconds']:.1f} s "
+                                          f"(bit-identical to the single-thread run, which took {cb['single_seconds']:.1f} s)",
+                                "GBps": cb["value"] * bytes_upd / 1e9,
+                                "single_thread": {"value": cb["single_value"], "cores": 1, "GBps": cb["single_value"] * bytes_upd / 1e9}}
     print(json.dumps(line))
 
 
