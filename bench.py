@@ -54,7 +54,7 @@ def run_gpu(w, steps, warmup, ring=64, flags=0, batch=1, windows=3, **launch):
 
     c = w.c
     learner, step = w.arrival_trace((warmup + windows * steps) * c)
-    hip = HipServer(w, flags=flags, pregenerated=max(ring, c + 1), **launch)
+    hip = HipServer(w, flags=flags, pregenerated=max(ring, c + 1, batch + c if batch > 1 else 0), **launch)   # a buffer is reused only after its update
     ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
     nbuf = len(bufs)
     learner_ts = [0] * w.n_learners
