@@ -338,6 +338,7 @@ def main():
                          "the headline is measured with 1 (every update its own launch)")
     ap.add_argument("--waves", type=int, default=0, help="launch_waves_per_cu")
     ap.add_argument("--state-loads", type=int, default=0, help="launch_state_loads")
+    ap.add_argument("--phased", action="store_true", help="launch_phased = 2: the phase-aligned kernel (opt-in; for many gradients per update)")
     ap.add_argument("--params", type=int, default=0, help="run the workload's recipe at another vector length (size sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the bandwidth probes, the per-kernel event pass and the other workloads")
@@ -370,7 +371,7 @@ def main():
         print(json.dumps({"stream_probes_GBps": run_stream_ceilings(n, [t.data_ptr() for t in pool], sink.data_ptr()), "n_floats": n}))
         return
     launch = dict(launch_block=args.block, launch_unroll=args.unroll, launch_vec=args.vec, launch_grid=args.grid,
-                  launch_waves_per_cu=args.waves, launch_state_loads=args.state_loads)
+                  launch_waves_per_cu=args.waves, launch_state_loads=args.state_loads, launch_phased=2 if args.phased else 0)
     w = configs.ALL[args.workload]
     if args.params:
         w = w.scaled(n_params=args.params, name=f"{w.name}@{args.params}")

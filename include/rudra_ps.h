@@ -127,6 +127,11 @@ typedef struct {
                                 velocity / AdaGrad sums, 3 the weights; 0 = library default (by c and by
                                 RUDRA_FLAG_DOUBLE_BUFFER, see the kernel header for the measurements).  Takes effect in the
                                 default launch shape (launch_vec 1, launch_unroll 1 or 4). */
+  uint32_t launch_phased;      /* 2: run single-update launches through the phase-aligned kernel (few persistent waves keep
+                                the running sums of their tiles in registers and the whole chip streams through one gradient
+                                at a time; not with RUDRA_FLAG_STATS_NORMS, not for launches fused by rudra_ps_push_batch).
+                                Same results to the bit.  0 or 1: off (the default): measured +1 to +6 % for 54-64 gradients
+                                per update on vectors of 72M parameters and more, slower everywhere else. */
 } rudra_ps_config_t;
 
 typedef struct {
@@ -166,6 +171,7 @@ typedef struct {
   uint64_t n_batched_updates; /* updates that shared a launch with at least one other update */
   uint64_t n_weight_acquires; /* rudra_ps_weights_acquire calls */
   uint64_t n_reader_waits;    /* reader events that applyUpdate launches were made to wait for (rudra_ps_weights_release) */
+  uint64_t n_phased_launches; /* updates that ran through the phase-aligned kernel (see launch_phased) */
 } rudra_ps_stats_t;
 
 /* Create a server.  init_weights: DEVICE pointer to P floats (checked with the HIP runtime), copied (the caller keeps its buffer); in

@@ -28,7 +28,7 @@ class Config(C.Structure):
                 ("stream", C.c_void_p), ("clock_ring", C.c_uint32), ("launch_block", C.c_uint32),
                 ("launch_unroll", C.c_uint32), ("launch_vec", C.c_uint32), ("launch_grid", C.c_uint32),
                 ("launch_waves_per_cu", C.c_uint32), ("max_aggregate", C.c_uint32), ("launch_alternate", C.c_uint32),
-                ("launch_state_loads", C.c_uint32)]
+                ("launch_state_loads", C.c_uint32), ("launch_phased", C.c_uint32)]
 
 
 class PushResult(C.Structure):
@@ -46,7 +46,7 @@ class Stats(C.Structure):
                 ("last_lr", C.c_float), ("norms_valid", C.c_int32), ("last_hip_error", C.c_int32),
                 ("reserved", C.c_uint32), ("n_weight_copies", C.c_uint64), ("n_ts_inquiries", C.c_uint64),
                 ("n_weight_views", C.c_uint64), ("n_apply_launches", C.c_uint64), ("n_batched_updates", C.c_uint64),
-                ("n_weight_acquires", C.c_uint64), ("n_reader_waits", C.c_uint64)]
+                ("n_weight_acquires", C.c_uint64), ("n_reader_waits", C.c_uint64), ("n_phased_launches", C.c_uint64)]
 
 
 _lib = None
@@ -126,11 +126,11 @@ class ParameterServer:
                  lr_mode=LR_AVG_STALENESS, alpha0=0.01, lr_scale=1.0, momentum=0.0, weight_decay=0.0,
                  c_override=0, device=0, stream=0, flags=0, clock_ring=0, launch_block=0, launch_unroll=0,
                  launch_vec=0, launch_grid=0, launch_waves_per_cu=0, launch_alternate=0, optimizer=OPT_SGD,
-                 adagrad_eps=1e-8, max_aggregate=0, launch_state_loads=0):
+                 adagrad_eps=1e-8, max_aggregate=0, launch_state_loads=0, launch_phased=0):
         self._L = lib()
         self.cfg = Config(n_params, n_learners, n_split, c_override, protocol, lr_mode, alpha0, lr_scale, momentum,
                           weight_decay, optimizer, adagrad_eps, device, flags, stream or None, clock_ring, launch_block, launch_unroll,
-                          launch_vec, launch_grid, launch_waves_per_cu, max_aggregate, launch_alternate, launch_state_loads)
+                          launch_vec, launch_grid, launch_waves_per_cu, max_aggregate, launch_alternate, launch_state_loads, launch_phased)
         h = C.c_void_p()
         rc = self._L.rudra_ps_create(C.byref(self.cfg), init_weights_ptr or None, C.byref(h))
         if rc != OK:

@@ -445,6 +445,122 @@ __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan
   if (STATS) block_reduce_norms(n, a.partials);
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------------
+// Phase-aligned variant for updates of MANY gradients.  Opt-in (launch_phased = 2): measured, and not a robust win.
+//
+// The kernels above let every wave walk the c gradients of its own tile, so at any moment the resident waves are spread
+// over all c + 2 streams; DRAM then serves c + 2 concurrently open streams, and the rate falls with c (read-only probes:
+// 3 streams 88 % of 8 TB/s, 20 streams 83 %; this path: c = 18 81 %, c = 54 78 %).  Here few persistent waves (as many as
+// are resident at once: 4 per SIMD) each own T tiles per pass, keep the T running sums in registers and walk the
+// gradients in the OUTER loop: the whole chip streams through gradient j, then through gradient j + 1, ... and only at
+// the end of the pass through theta and v.  D loads are kept in flight per wave across tiles and across gradients (the
+// first D tiles of the next gradient are requested while the last tiles of the current one are summed).  The vector is
+// covered in n_passes passes of gridDim.x * T tiles of 64 float4 positions: in pass p, wave w owns the tiles
+// (p * gridDim.x * T) + t * gridDim.x + w, t = 0..T-1, so that the waves sweep each stream front to back together.
+// The host launches it on the largest prefix of the vector that is a whole number of such passes and runs the ordinary
+// kernel on the rest (less than T * n_passes tiles).  Per element the operations and their order are those of
+// apply_update_kernel: same bits.
+// Measured against apply_update_kernel in one process (T = 25, D = 5): 72M parameters c = 40 / 48 / 54 / 64: 0 / +1 / +1 to
+// +5 / +4 to +6 %; 144M: -0.5 / +2 / +2.6 / +4 %; 100M: -3.4 / -0.6 / -1.4 / +1.4 %; 36M: -2 to -6 %; c = 30 -3 %, c = 18 -8 %
+// (the pass epilogue over theta and v runs with few requests in flight; it is 18 % of the bytes at c = 18, 7 % at c = 54).
+// Other (T, D) that fit the registers are 3 to 8 % SLOWER than apply_update_kernel (24/4, 20/4, 16/4 at 4 waves per SIMD,
+// 32/4 and 28/4 at 3, 40/4 and 48/4 at 2): the gain is small, confined to the largest c and vectors, and sensitive to the
+// tiling, hence not the default.
+#ifndef RUDRA_PHASED_T   // (overridable at build time for tuning runs)
+#define RUDRA_PHASED_T 25
+#define RUDRA_PHASED_D 5
+#define RUDRA_PHASED_WPS 4
+#endif
+constexpr int kPhasedTiles = RUDRA_PHASED_T;          // T: 4T registers of running sums per lane
+constexpr int kPhasedDepth = RUDRA_PHASED_D;          // D: gradient loads in flight per lane; must divide T (ring slots are reused in order)
+constexpr int kPhasedWavesPerSimd = RUDRA_PHASED_WPS;  // 512 / this many registers per lane
+static_assert(kPhasedTiles % kPhasedDepth == 0 && kPhasedDepth >= 2, "ring slots are reused in tile order");
+
+// One gradient's phase for one wave: add its T tiles into s, keeping D requests in flight; the last D requests go to the
+// next gradient's first tiles (MORE) so the queue never drains between gradients.  The empty asm keeps the compiler from
+// hoisting later requests above earlier sums (it would need registers for all of them at once).
+template <int T, int D, bool FIRST, bool MORE, bool WEIGHTED>
+__device__ __forceinline__ void phased_accumulate(floatx4 (&s)[T], floatx4 (&ring)[D], const floatx4* q, const floatx4* qn,
+                                                  uint64_t step, float w) {
+#pragma unroll
+  for (int t = 0; t < T - D; ++t) {
+    floatx4 g = ring[t % D];
+    if (WEIGHTED) g = g * w;
+    if (FIRST) s[t] = g; else s[t] = s[t] + g;
+    ring[t % D] = __builtin_nontemporal_load(q);
+    q += step;
+    asm volatile("" ::: "memory");
+  }
+#pragma unroll
+  for (int t = T - D; t < T; ++t) {
+    floatx4 g = ring[t % D];
+    if (WEIGHTED) g = g * w;
+    if (FIRST) s[t] = g; else s[t] = s[t] + g;
+    if (MORE) { ring[t % D] = __builtin_nontemporal_load(qn); qn += step; }
+    asm volatile("" ::: "memory");
+  }
+}
+
+template <int OPT, bool DECAY, bool WEIGHTED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(kPhasedWavesPerSimd, kPhasedWavesPerSimd)))
+void apply_update_phased_kernel(const GradSet gs, const UpdateArgs a, uint32_t n_passes) {
+  constexpr int T = kPhasedTiles, D = kPhasedDepth, H = D / 2;
+  const uint64_t nw = gridDim.x, w = blockIdx.x;
+  const uint64_t step = nw * 64;  // float4 positions from one tile of this wave to its next
+  const uint32_t c = a.c;
+  Norms unused = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t pass0 = 0; pass0 < n_passes; ++pass0) {
+    const uint32_t pass = a.reverse ? n_passes - 1 - pass0 : pass0;
+    const uint64_t first = ((uint64_t)pass * nw * T + w) * 64 + threadIdx.x;  // this lane's position in its wave's tile 0
+    floatx4 s[T], ring[D];
+    const floatx4* gcur = reinterpret_cast<const floatx4*>(gs.p[0]) + first;
+    {
+      const floatx4* q = gcur;
+#pragma unroll
+      for (int t = 0; t < D; ++t) { ring[t] = __builtin_nontemporal_load(q); q += step; }
+      asm volatile("" ::: "memory");
+    }
+    if (c == 1) {
+      phased_accumulate<T, D, true, false, WEIGHTED>(s, ring, gcur + (uint64_t)D * step, gcur, step, gs.w[0]);
+    } else {
+      const floatx4* gnext = reinterpret_cast<const floatx4*>(gs.p[1]) + first;
+      phased_accumulate<T, D, true, true, WEIGHTED>(s, ring, gcur + (uint64_t)D * step, gnext, step, gs.w[0]);
+      gcur = gnext;
+      for (uint32_t j = 1; j + 1 < c; ++j) {
+        gnext = reinterpret_cast<const floatx4*>(gs.p[j + 1]) + first;
+        phased_accumulate<T, D, false, true, WEIGHTED>(s, ring, gcur + (uint64_t)D * step, gnext, step, gs.w[j]);
+        gcur = gnext;
+      }
+      phased_accumulate<T, D, false, false, WEIGHTED>(s, ring, gcur + (uint64_t)D * step, gcur, step, gs.w[c - 1]);
+    }
+    // the pass's applyUpdate: theta and v of the T tiles, H tiles requested ahead (the ring's registers are free now)
+    const floatx4* tq = reinterpret_cast<const floatx4*>(a.theta) + first;
+    const floatx4* vq = reinterpret_cast<const floatx4*>(a.vel) + first;
+    floatx4* to = reinterpret_cast<floatx4*>(a.theta_out) + first;
+    floatx4* vo = reinterpret_cast<floatx4*>(a.vel) + first;
+#pragma unroll
+    for (int t = 0; t < H; ++t) {
+      ring[t] = *tq; tq += step;
+      if (OPT != kOptSgd) { ring[H + t] = *vq; vq += step; }
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      floatx4 th = ring[t % H], ve = {0.f, 0.f, 0.f, 0.f};
+      if (OPT != kOptSgd) ve = ring[H + t % H];
+      if (t + H < T) {
+        ring[t % H] = *tq; tq += step;
+        if (OPT != kOptSgd) { ring[H + t % H] = *vq; vq += step; }
+      }
+      update_vec4<OPT, DECAY, false>(s[t], th, ve, a, unused);
+      __builtin_nontemporal_store(th, to); to += step;
+      if (OPT != kOptSgd) { __builtin_nontemporal_store(ve, vo); vo += step; }
+      asm volatile("" ::: "memory");
+    }
+  }
+}
+
 // sumGradients alone: sum_out[k] = w_1*g_1[k] + ... in arrival order.  Used when a gradient is
 // accumulated at push time and to fold sets of more than kMaxFused gradients; sum_out may be
 // the same buffer as gs.p[0] (each position is read, then written, by one lane).

@@ -118,6 +118,8 @@ struct rudra_ps {
   // launch shape
   uint32_t block = kDefaultBlock, unroll = kDefaultUnroll, vec = kDefaultVec, grid_cap = 0, waves_per_cu = 0;
   bool alternate = true;
+  uint32_t n_cus = 256;             // compute units of the device (the phase-aligned kernel launches as many waves as are resident at once)
+  uint64_t n_phased_launches = 0;
 
   // protocol state
   uint64_t ts_cur = 0;
@@ -447,6 +449,48 @@ void after_apply_launch(rudra_ps* ps, uint32_t grid) {
   if (ps->double_buffer) ps->cur ^= 1u;  // the pointer swap: the buffer just written now holds the current weights
 }
 
+// ---- phase-aligned launch for updates of many gradients (apply_update_phased_kernel) ----
+struct PhasedPlan {
+  uint32_t n_waves, n_passes;
+  uint64_t body_params;  // parameters the phased launch covers: n_waves * kPhasedTiles * n_passes tiles of 256
+};
+
+// The largest prefix of the vector that is a whole number of passes of n_waves * T tiles, with n_waves at most what is
+// resident at once; {0, 0, 0} when the vector has fewer than T tiles.
+PhasedPlan phased_plan(uint64_t n_params, uint32_t n_cus) {
+  const uint64_t tiles = n_params / 256;  // whole tiles of 64 float4
+  const uint64_t T = (uint64_t)rudra::kPhasedTiles;
+  const uint64_t cap = (uint64_t)n_cus * 4u * (uint64_t)rudra::kPhasedWavesPerSimd;
+  if (tiles < T) return {0, 0, 0};
+  const uint64_t passes = (tiles + cap * T - 1) / (cap * T);
+  const uint64_t waves = tiles / (T * passes);  // <= cap
+  if (waves == 0 || passes > 0xFFFFFFFFull) return {0, 0, 0};
+  return {(uint32_t)waves, (uint32_t)passes, waves * T * passes * 256};
+}
+
+template <int OPT>
+void launch_phased_o(bool decay, bool weighted, const PhasedPlan& pl, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  const dim3 g(pl.n_waves), b(64);
+  if (decay) {
+    if (weighted) hipLaunchKernelGGL((rudra::apply_update_phased_kernel<OPT, true, true>), g, b, 0, st, gs, a, pl.n_passes);
+    else hipLaunchKernelGGL((rudra::apply_update_phased_kernel<OPT, true, false>), g, b, 0, st, gs, a, pl.n_passes);
+  } else {
+    if (weighted) hipLaunchKernelGGL((rudra::apply_update_phased_kernel<OPT, false, true>), g, b, 0, st, gs, a, pl.n_passes);
+    else hipLaunchKernelGGL((rudra::apply_update_phased_kernel<OPT, false, false>), g, b, 0, st, gs, a, pl.n_passes);
+  }
+}
+void launch_phased(int opt, bool decay, bool weighted, const PhasedPlan& pl, hipStream_t st, const GradSet& gs, const UpdateArgs& a) {
+  switch (opt) {
+    case rudra::kOptMomentum: launch_phased_o<rudra::kOptMomentum>(decay, weighted, pl, st, gs, a); break;
+    case rudra::kOptAdagrad: launch_phased_o<rudra::kOptAdagrad>(decay, weighted, pl, st, gs, a); break;
+    default: launch_phased_o<rudra::kOptSgd>(decay, weighted, pl, st, gs, a); break;
+  }
+}
+
+// Whether this update goes through the phase-aligned kernel: only on the caller's request (launch_phased = 2; it is not
+// a robust win, see the kernel's header) and never with fused norms (it has no reduction epilogue).
+bool use_phased(const rudra_ps* ps) { return ps->cfg.launch_phased == 2 && !ps->want_norms; }
+
 // sumGradients + applyUpdate for the `n` pending messages in `g` standing for `count` learner gradients (Eq. 3 /
 // Eq. 5), one fused launch when n <= kMaxFused.
 int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count, float lr, bool weighted) {
@@ -485,7 +529,30 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
   if (rc != RUDRA_OK) return rc;
   rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
-  launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, state_load_policy(ps, n), ps->unroll, ps->vec, s, ps->stream, gs, a);
+  PhasedPlan pl = {0, 0, 0};
+  if (use_phased(ps)) pl = phased_plan(ps->cfg.n_params, ps->n_cus);
+  if (pl.body_params) {
+    // the phase-aligned kernel on the prefix it tiles exactly, the ordinary kernel on what is left (same arithmetic)
+    launch_phased(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, pl, ps->stream, gs, a);
+    RUDRA_HIP(ps, hipGetLastError());
+    ps->n_phased_launches += 1;
+    const uint64_t rest = ps->cfg.n_params - pl.body_params;
+    if (rest) {
+      GradSet gr = gs;
+      for (uint32_t j = 0; j < n; ++j) gr.p[j] = gs.p[j] + pl.body_params;
+      UpdateArgs ar = a;
+      ar.theta = a.theta + pl.body_params;
+      ar.theta_out = a.theta_out + pl.body_params;
+      if (a.vel) ar.vel = a.vel + pl.body_params;
+      ar.n_params = rest;
+      const uint64_t tile = (uint64_t)ps->block * ps->vec;
+      ar.ntiles = ((rest >> 2) + tile - 1) / tile;
+      const LaunchShape sr = {grid_for(ar.ntiles, ps->block, ps->grid_cap), ps->block, ar.ntiles, 0};
+      launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, false, rudra::kStateLoadsCached, ps->unroll, ps->vec, sr, ps->stream, gr, ar);
+    }
+  } else {
+    launch_apply(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, state_load_policy(ps, n), ps->unroll, ps->vec, s, ps->stream, gs, a);
+  }
   RUDRA_HIP(ps, hipGetLastError());
   rc = end_timed(ps, slot);
   if (rc != RUDRA_OK) return rc;
@@ -652,7 +719,7 @@ int validate_config(const rudra_ps_config_t* c) {
   if (c->launch_unroll && c->launch_unroll != 1 && c->launch_unroll != 2 && c->launch_unroll != 4 && c->launch_unroll != 8)
     return RUDRA_EINVAL;
   if (c->launch_vec && c->launch_vec != 1 && c->launch_vec != 2 && c->launch_vec != 4) return RUDRA_EINVAL;
-  if (c->launch_alternate > 2 || c->launch_state_loads > 3) return RUDRA_EINVAL;
+  if (c->launch_alternate > 2 || c->launch_state_loads > 3 || c->launch_phased > 2) return RUDRA_EINVAL;
   if (c->max_aggregate > 1 && c->lr_mode == RUDRA_LR_PER_GRADIENT) return RUDRA_EINVAL;  // a relayed average cannot be re-weighted
   if (c->max_aggregate > 4096) return RUDRA_EINVAL;
   if (c->launch_waves_per_cu && (c->launch_waves_per_cu < 2 || c->launch_waves_per_cu > 32)) return RUDRA_EINVAL;
@@ -739,6 +806,11 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
     if (e == hipSuccess && !is_device_range(init_weights, bytes, config->device)) {
       delete ps;
       return RUDRA_EINVAL;  // not P floats of this device's memory
+    }
+    if (e == hipSuccess) {
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, config->device) == hipSuccess && cus > 0) ps->n_cus = (uint32_t)cus;
+      else (void)hipGetLastError();
     }
     if (e == hipSuccess) e = hipMalloc((void**)&ps->theta2[0], bytes);
     if (e == hipSuccess && ps->double_buffer) e = hipMalloc((void**)&ps->theta2[1], bytes);
@@ -1185,6 +1257,7 @@ int rudra_ps_stats(rudra_ps_t* ps, rudra_ps_stats_t* out) {
   out->n_batched_updates = ps->n_batched_updates;
   out->n_weight_acquires = ps->n_weight_acquires;
   out->n_reader_waits = ps->n_reader_waits;
+  out->n_phased_launches = ps->n_phased_launches;
   if (ps->failed) return RUDRA_EHIP;
   if (ps->time_kernels) {
     DeviceGuard guard(ps->cfg.device);

@@ -292,3 +292,57 @@ def test_state_load_policies_give_the_same_bits(hipmod, state_loads, double_buff
     hip, ora = _run_both_batched(hipmod, w, [7, 20, 50], flags=flags, launch_state_loads=state_loads)
     _compare(hip, ora, w)
     hip.close()
+
+
+# ---------------------------------------------------------------- the phase-aligned kernel (opt-in): same bits as the ordinary one
+@pytest.mark.parametrize("case", ["c1-sgd", "c2-momentum-decay", "c7-adagrad-decay", "c41-momentum", "c64-per-gradient-weights", "c70-fold",
+                                  "double-buffer", "tree-root", "hardsync"])
+def test_phased_kernel_gives_the_oracle_bits(hipmod, case):
+    """launch_phased = 2: few persistent waves keep the running sums of their tiles in registers and walk the gradients in
+    the outer loop; the ordinary kernel takes what is left of the vector behind the last whole pass.  Vector lengths span
+    less than one wave's tiles (all ordinary), one pass with a ragged rest, and several tiles per wave."""
+    from paper_1509_04210_amd import binding as B
+    from tests.test_gpu_parity import _compare, _run_both
+    sizes = [5_003, 6_400 * 7 + 3, 300_001, 1_000_000]       # 25 tiles of 256 parameters make one wave's pass
+    base = {"c1-sgd": _with(configs.C3(30).scaled(n_pushes=40)),
+            "c2-momentum-decay": _with(configs.C5.scaled(n_pushes=60), n_learners=6, n_split=3),
+            "c7-adagrad-decay": _with(configs.C3(4).scaled(n_pushes=7 * 5 + 3), optimizer="adagrad", weight_decay=5e-4),
+            "c41-momentum": _with(configs.C4.scaled(n_pushes=41 * 3), n_learners=41),
+            "c64-per-gradient-weights": _with(configs.C3(1).scaled(n_pushes=64 * 3 + 5), n_learners=64, lr_mode="per_gradient", momentum=0.9, straggler_prob=0.3),
+            "c70-fold": _with(configs.C3(1).scaled(n_pushes=70 * 3), n_learners=70, momentum=0.9, weight_decay=5e-4),
+            "double-buffer": _with(configs.C4.scaled(n_pushes=18 * 5)),
+            "hardsync": configs.C2.scaled(n_pushes=30 * 4)}
+    if case == "tree-root":
+        lam, fan_in = 12, 3
+        for P in sizes[1:3]:
+            w = _with(configs.C4.scaled(n_params=P, n_pushes=lam * 4), n_learners=lam)
+            learner, step = w.arrival_trace()
+            hip = hipmod.HipServer(w, ring=2 * fan_in + 2, avg_ring=lam // fan_in + 4, max_aggregate=fan_in, launch_phased=2)
+            ora = OracleServer(w, max_aggregate=fan_in)
+            lh = replay.replay_tree(hip, learner, step, lam, fan_in)
+            lo = replay.replay_tree(ora, learner, step, lam, fan_in)
+            for k in lo:
+                assert np.array_equal(lh[k], lo[k]), k
+            _compare_tree(hip, ora, w)
+            assert hip.ps.stats().n_phased_launches == ora.ps.ts >= 3
+            hip.close()
+        return
+    flags = B.FLAG_DOUBLE_BUFFER if case == "double-buffer" else 0
+    for P in sizes:
+        w = base[case].scaled(n_params=P)
+        hip, ora = _run_both(hipmod, w, flags=flags, launch_phased=2, launch_alternate=0 if P % 2 else 2)
+        _compare(hip, ora, w)
+        st = hip.ps.stats()
+        assert st.n_phased_launches == (st.n_updates if P >= 6_400 else 0)      # fewer than 25 whole tiles: nothing to phase
+        hip.close()
+
+
+def test_phased_kernel_is_not_used_with_fused_norms_or_by_default(hipmod):
+    from paper_1509_04210_amd import binding as B
+    from tests.test_gpu_parity import _compare, _run_both
+    w = _with(configs.C4.scaled(n_params=300_001, n_pushes=45 * 2), n_learners=45)
+    for kw, want in ((dict(launch_phased=2, flags=B.FLAG_STATS_NORMS), 0), (dict(), 0), (dict(launch_phased=1), 0), (dict(launch_phased=2), 2)):
+        hip, ora = _run_both(hipmod, w, **kw)
+        _compare(hip, ora, w)
+        assert hip.ps.stats().n_phased_launches == want
+        hip.close()
