@@ -308,6 +308,8 @@ int rudra_ps_vector_clock(rudra_ps_t* ps, uint64_t update_idx, uint64_t* ts_out,
  *              the update, valid once the work enqueued on `stream` has run
  * Arithmetic and bits of theta and state are those of the server path.  Limits: c <= 64 and P <= 134 217 728
  * (one norm slot per 1024-parameter tile); beyond either the call returns ERANGE and does nothing.
+ * The first call on a device looks up that device's copy of the array (one hipGetSymbolAddress, no allocation): a caller
+ * that records a HIP graph makes one call outside the capture first.
  * All calls on one GPU share that GPU's slot array: calls whose device work can overlap (different streams without
  * ordering between them) race on it and must be serialised by the caller; nothing in it needs clearing between calls.
  * Errors: EINVAL (null / misaligned pointer, c = 0, P = 0, bad optimizer or device), ERANGE, EHIP. */
