@@ -85,7 +85,7 @@ enum : int { kStateLoadsCached = 0, kStateLoadsVelNt = 1, kStateLoadsThetaNt = 2
 // Launch shape: one 64-lane wavefront per workgroup (6-8 % faster than 256-thread workgroups), and the host caps the
 // resident waves per CU by reserving unused LDS: what counts is the volume of loads in flight per CU and, at equal
 // volume, that few tiles are open at once (more concurrently open tiles keep more DRAM pages open and lose 3-6 %).
-// Measured optimum: c <= 4: all loads of a wave in one round, 12-16 waves; c > 4: ONE gradient load at a time per wave
+// Measured optimum: c <= 4: all loads of a wave in one round, 16 waves; c > 4: ONE gradient load at a time per wave
 // (U = 1) and 26 waves.  Keeping 2-4 gradient loads rolling per wave, lanes that own 2-4 tiles (adjacent or strided),
 // per-XCD contiguous regions and grid-stride persistence were all measured and are slower or equal.
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {

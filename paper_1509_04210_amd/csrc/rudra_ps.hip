@@ -224,8 +224,9 @@ uint32_t grid_for(uint64_t tiles, uint32_t block, uint32_t cap) {
 // Measured at 72M parameters (GB/s of algorithmic bytes, medians): what counts is how many loads are in flight per
 // CU, about kInFlightKiBPerCu KiB at 1 KiB per wave-load, and, at equal volume, that few tiles are open at once.
 //   c <= unroll (4): a wave issues theta, the second state vector and all its gradients in one round; 48/(loads per
-//           wave) resident waves, at least 12 (c = 1: 16 waves 7.0 TB/s; c = 2: 12 waves 7.0; c = 4: 12 waves 6.7-6.8,
-//           8 waves 6.2-6.3).
+//           wave) resident waves, at least 16 (with the velocity loaded non-temporally, 8 / 10 / 12 / 16 / 20 waves:
+//           c = 2 6.36 / 6.44 / 6.80 / 7.22 / 7.15 TB/s, c = 3 6.45 / 6.70 / 7.05 / 7.14 / 7.12, c = 4 6.21 / 6.54 / 6.96 /
+//           7.16 / 7.15; c = 1: 12 / 16 / 20 / 26 waves 6.69 / 7.16 / 7.16 / 7.06).
 //   c > 4 with the default unroll of 1: after the first round a wave has one gradient load outstanding, and 26
 //           resident waves are best (c = 7: 6.78, c = 18: 6.41, c = 30: 6.13, c = 54: 6.22; 20 or 32 waves lose
 //           2-4 %; 4 loads at a time with 8 waves is 1-2 % behind); small vectors run uncapped (kSmallVector).
@@ -234,7 +235,7 @@ uint32_t default_waves_per_cu(uint32_t c, uint32_t unroll, int optimizer, uint64
   const uint32_t per_wave = std::min(c, unroll) + 1u + (optimizer != rudra::kOptSgd ? 1u : 0u);
   const uint32_t waves_per_wg = block / 64;
   uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
-  if (c <= unroll) w = std::max(w, 12u);
+  if (c <= unroll) w = std::max(w, 16u);
   else if (unroll == 1) w = n_params < kSmallVector ? 32 : 26;
   w = std::max(w, std::max(4u, waves_per_wg));
   return std::min(w, 32u);
@@ -309,8 +310,9 @@ void launch_apply(int opt, bool decay, bool weighted, bool stats, int ntld, uint
 //   two weight buffers: the weights, always (the buffer read is dead once the update has run): c = 1 0.86 / 0.77-0.80 /
 //     0.89, c = 18 0.80 / 0.78 / 0.82: the double buffer then costs nothing against updating in place.
 //   in place, one update per launch: c = 1 0.887 / 0.905 / 0.903; c = 3 ... 14 +1.5 to +3.5 % for either (c = 5: 0.854 /
-//     0.887 / 0.886; c = 12: 0.826 / 0.839 / 0.839); c = 2 is the exception, on both machines (0.875 / 0.850 / 0.849);
-//     c >= 16 within 1 % either way (c = 18: 0.812 / 0.816 / 0.817; c = 30: 0.78 / 0.76-0.78 / 0.78).  The velocity is taken.
+//     0.887 / 0.886; c = 12: 0.826 / 0.839 / 0.839); c = 2 looked like an exception at 12 resident waves (0.875 / 0.850)
+//     but not at the 16 it runs with now (0.891 / 0.902); c >= 16 within 1 % either way (c = 18: 0.812 / 0.816 / 0.817;
+//     c = 30: 0.78 / 0.76-0.78 / 0.78).  The velocity is taken, up to 14 gradients.
 //   plain SGD (no second state vector): ordinary loads (c = 1: 0.881 vs 0.864; c = 18: 0.821 vs 0.809).
 //   several updates per launch: up to about 40 gradients per launch the weights non-temporal is +1 to +6 % (varies
 //     with the machine, never below -1 %), beyond that ordinary loads are equal or 1 % better.
@@ -318,7 +320,7 @@ int state_load_policy(const rudra_ps* ps, uint32_t n_grads) {
   if (ps->cfg.launch_state_loads) return (int)ps->cfg.launch_state_loads - 1;
   if (ps->double_buffer) return rudra::kStateLoadsThetaNt;
   if (kernel_optimizer(ps->cfg) == rudra::kOptSgd) return rudra::kStateLoadsCached;
-  if (n_grads == 1 || (n_grads >= 3 && n_grads <= 14)) return rudra::kStateLoadsVelNt;
+  if (n_grads <= 14) return rudra::kStateLoadsVelNt;
   return rudra::kStateLoadsCached;
 }
 int batch_state_load_policy(const rudra_ps* ps, uint32_t n_grads) {
