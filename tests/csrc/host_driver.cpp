@@ -104,9 +104,73 @@ int main() {
   CHECK(rudra_ps_push_gradient(ps, nullptr, 0, 6, &r) == RUDRA_OK && r.applied && r.ts_after == 1);
   CHECK(rudra_ps_push_gradient(ps, nullptr, 0, 0, &r) == RUDRA_EHARDSYNC_STALE);
   CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+  // relayed averages (server tree): several timestamps per message, overshoot of c under softsync, none under hardsync
+  cfg.max_aggregate = 3;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_OK);  // hardsync, lambda = 7
+  {
+    const uint64_t zeros[4] = {0, 0, 0, 0};
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 3, &r) == RUDRA_OK && r.pending == 3);
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 3, &r) == RUDRA_OK && r.pending == 6);
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 2, &r) == RUDRA_EHARDSYNC_DUP);  // 8 > lambda
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 4, &r) == RUDRA_EINVAL);         // more than max_aggregate
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 1, &r) == RUDRA_OK && r.applied && r.ts_after == 1);
+    uint64_t clk[9]; uint32_t cn = 0;
+    CHECK(rudra_ps_vector_clock(ps, 0, clk, 9, &cn, nullptr, nullptr) == RUDRA_OK && cn == 7);
+  }
+  CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+  cfg.protocol = RUDRA_SOFTSYNC;  // c = 3, messages of up to 3: an update can collect 5
+  cfg.lr_mode = RUDRA_LR_AVG_STALENESS;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_OK);
+  {
+    const uint64_t zeros[3] = {0, 0, 0};
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 2, &r) == RUDRA_OK && !r.applied);
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, zeros, 3, &r) == RUDRA_OK && r.applied && r.pending == 0);
+    uint64_t clk[5]; uint32_t cn = 0;
+    CHECK(rudra_ps_vector_clock(ps, 0, clk, 5, &cn, nullptr, nullptr) == RUDRA_OK && cn == 5);
+    const uint64_t future[1] = {9};
+    CHECK(rudra_ps_push_aggregate(ps, nullptr, future, 1, &r) == RUDRA_EFUTURE_TS);
+    // what needs device memory says so in control-only mode
+    const float* p = nullptr; uint64_t ticket = 0;
+    CHECK(rudra_ps_weights_acquire(ps, nullptr, &p, nullptr, &ticket) == RUDRA_ESTATE);
+    CHECK(rudra_ps_weights_release(ps, 0, nullptr) == RUDRA_ESTATE);
+    float f;
+    CHECK(rudra_ps_pull_velocity(ps, &f) == RUDRA_ESTATE);
+    uint32_t grid = 0, block = 0, lds = 0; uint64_t tiles = 0;
+    CHECK(rudra_ps_launch_shape(ps, 0, &grid, &block, &tiles, &lds) == RUDRA_OK && block == 64 && tiles == 4 && grid == 4);   // 250 float4 in tiles of 64
+    CHECK(rudra_ps_launch_shape(ps, 1, &grid, nullptr, nullptr, nullptr) == RUDRA_OK && grid == 4);
+  }
+  CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+  cfg.max_aggregate = 0;
+  // configurations that are refused
   cfg.n_split = 9;
-  cfg.protocol = RUDRA_SOFTSYNC;
   CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL && ps == nullptr);
+  cfg.n_split = 2;
+  cfg.lr_scale = 0.0f;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL);
+  cfg.lr_scale = 1.0f;
+  cfg.launch_state_loads = 4;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL);
+  cfg.launch_state_loads = 0;
+  cfg.launch_phased = 3;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL);
+  cfg.launch_phased = 0;
+  cfg.n_learners = 1u << 25;  // a vector clock of 2^25 entries
+  cfg.n_split = 1;
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL);
+  cfg.n_learners = 4; cfg.c_override = 0xFFFFFFFFu; cfg.max_aggregate = 4096;   // c + max_aggregate - 1 would wrap in 32 bits
+  CHECK(rudra_ps_create(&cfg, nullptr, &ps) == RUDRA_EINVAL);
+  // the entry point that allocates nothing rejects bad arguments before it touches a device
+  {
+    float x[4] = {0, 0, 0, 0}; double nrm[4];
+    const float* one[1] = {x};
+    CHECK(rudra_ps_apply_update_noalloc(nullptr, 1, 4, x, x, 0.1f, 0.f, 0.f, RUDRA_OPT_SGD, 0.f, nrm, 0, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_apply_update_noalloc(one, 65, 4, x, x, 0.1f, 0.f, 0.f, RUDRA_OPT_SGD, 0.f, nrm, 0, nullptr) == RUDRA_ERANGE);
+    CHECK(rudra_ps_apply_update_noalloc(one, 1, (1ull << 27) + 1, x, x, 0.1f, 0.f, 0.f, RUDRA_OPT_SGD, 0.f, nrm, 0, nullptr) == RUDRA_ERANGE);
+    CHECK(rudra_ps_apply_update_noalloc(one, 1, 4, x, nullptr, 0.1f, 0.9f, 0.f, RUDRA_OPT_SGD, 0.f, nrm, 0, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_apply_update_noalloc(one, 1, 4, x, x, 0.1f, 0.9f, 0.f, RUDRA_OPT_ADAGRAD, 0.f, nrm, 0, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_apply_update_noalloc(one, 1, 4, x, x, 0.1f, 0.f, 0.f, 7, 0.f, nrm, 0, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_apply_update_noalloc(one, 1, 4, x, x, 0.1f, 0.f, 0.f, RUDRA_OPT_SGD, 0.f, nrm, -1, nullptr) == RUDRA_EINVAL);
+  }
   std::printf("host driver ok\n");
   return 0;
 }
