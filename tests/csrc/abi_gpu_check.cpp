@@ -175,6 +175,64 @@ int main() {
     (void)hipFree(out);
   }
 
+  // --- the entry point that allocates nothing: one update of c = 2 gradients (1 and 3: mean 2) on the caller's own theta = 1
+  //     and v = 0 with alpha = 1/4, m = 1/2: v = -1/2, theta = 1/2; norms: sum gbar^2 = 4P, sum theta^2 = P/4, sum v^2 = P/4,
+  //     max |theta| = 1/2 (all exact in binary64); then a second call on the same state: v = -1/4 - 1/2 = -3/4, theta = -1/4
+  {
+    float* theta = device_constant(1.0f);
+    float* vel = device_constant(0.0f);
+    double* norms = nullptr;
+    CHECK(theta && vel && hipMalloc((void**)&norms, 4 * sizeof(double)) == hipSuccess);
+    const float* pair[2] = {one, three};
+    double h[4];
+    CHECK(rudra_ps_apply_update_noalloc(pair, 2, P, theta, vel, 0.25f, 0.5f, 0.0f, RUDRA_OPT_SGD, 0.0f, norms, 0, nullptr) == RUDRA_OK);
+    CHECK(hipMemcpy(h, norms, sizeof(h), hipMemcpyDeviceToHost) == hipSuccess);
+    CHECK(h[0] == 4.0 * P && h[1] == 0.25 * P && h[2] == 0.25 * P && h[3] == 0.5);
+    CHECK(rudra_ps_apply_update_noalloc(pair, 2, P, theta, vel, 0.25f, 0.5f, 0.0f, RUDRA_OPT_SGD, 0.0f, norms, 0, nullptr) == RUDRA_OK);
+    CHECK(hipMemcpy(h, norms, sizeof(h), hipMemcpyDeviceToHost) == hipSuccess);
+    CHECK(h[0] == 4.0 * P && h[1] == 0.0625 * P && h[2] == 0.5625 * P && h[3] == 0.25);
+    std::vector<float> ht(P), hv(P);
+    CHECK(hipMemcpy(ht.data(), theta, P * sizeof(float), hipMemcpyDeviceToHost) == hipSuccess);
+    CHECK(hipMemcpy(hv.data(), vel, P * sizeof(float), hipMemcpyDeviceToHost) == hipSuccess);
+    for (uint64_t k = 0; k < P; ++k) CHECK(ht[k] == -0.25f && hv[k] == -0.75f);
+    (void)hipFree(theta); (void)hipFree(vel); (void)hipFree(norms);
+  }
+
+  // --- a reader on its own stream (Sec. 3.3: communication buffer): with two weight buffers it takes the weights of
+  //     timestamp 1 (theta = 1 - 1/4 = 3/4 after one update with g = 1, alpha = 1/4), two more updates are enqueued (the
+  //     second overwrites that buffer and must wait for the reader), and its copy still holds 3/4 everywhere
+  {
+    rudra_ps_config_t c = base_config();
+    c.n_learners = 1;
+    c.alpha0 = 0.25f;
+    c.flags = RUDRA_FLAG_DOUBLE_BUFFER;
+    hipStream_t server, reader;
+    CHECK(hipStreamCreate(&server) == hipSuccess && hipStreamCreate(&reader) == hipSuccess);
+    c.stream = server;
+    rudra_ps_t* ps = nullptr;
+    CHECK(rudra_ps_create(&c, one, &ps) == RUDRA_OK);
+    CHECK(rudra_ps_push_gradient(ps, one, 0, 0, &r) == RUDRA_OK && r.applied);
+    const float* view = nullptr;
+    uint64_t ts = 0, ticket = 0;
+    CHECK(rudra_ps_weights_acquire(ps, reader, &view, &ts, &ticket) == RUDRA_OK && ts == 1 && view);
+    float* copy = device_constant(0.0f);
+    CHECK(copy && hipMemcpyAsync(copy, view, P * sizeof(float), hipMemcpyDeviceToDevice, reader) == hipSuccess);
+    CHECK(rudra_ps_weights_release(ps, ticket, reader) == RUDRA_OK);
+    CHECK(rudra_ps_push_gradient(ps, one, 1, 0, &r) == RUDRA_OK && r.applied);
+    CHECK(rudra_ps_push_gradient(ps, one, 2, 0, &r) == RUDRA_OK && r.applied);
+    CHECK(rudra_ps_weights_release(ps, ticket, reader) == RUDRA_ESTATE);   // the overwriting launch is enqueued: too late now
+    CHECK(hipStreamSynchronize(reader) == hipSuccess && rudra_ps_sync(ps) == RUDRA_OK);
+    std::vector<float> hc(P);
+    CHECK(hipMemcpy(hc.data(), copy, P * sizeof(float), hipMemcpyDeviceToHost) == hipSuccess);
+    for (uint64_t k = 0; k < P; ++k) CHECK(hc[k] == 0.75f);
+    CHECK(all_equal(ps, scratch, 0.25f));
+    rudra_ps_stats_t st;
+    CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK && st.n_weight_acquires == 1 && st.n_reader_waits == 1);
+    CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
+    (void)hipFree(copy);
+    (void)hipStreamDestroy(server); (void)hipStreamDestroy(reader);
+  }
+
   (void)hipFree(one); (void)hipFree(three); (void)hipFree(zero); (void)hipFree(scratch);
   std::printf("abi gpu check ok\n");
   return 0;
