@@ -109,7 +109,11 @@ typedef struct {
   /* launch shape of the fused kernel; 0 = library default.  Results do not depend on it, except the order in
      which the optional norms are reduced. */
   uint32_t launch_block;  /* threads per workgroup: 64..1024, multiple of 64 */
-  uint32_t launch_unroll; /* gradient loads issued together per lane: 1, 2, 4 or 8 */
+  uint32_t launch_unroll; /* gradient loads issued together per lane: 1, 2, 4 or 8.  0 = library default: everything at
+                             once up to 4 gradients per update, beyond that one at a time, except on short vectors (fewer
+                             tiles of 64 float4 than the chip holds resident wavefronts), which take 2, 4 or 8.  Launches
+                             fused by rudra_ps_push_batch: 4 or 8 = that many per round, 1 or 2 = one load ahead of the
+                             arithmetic (0 = by vector length) */
   uint32_t launch_vec;    /* float4 vectors per lane per tile: 1, 2 or 4 */
   uint32_t launch_grid;   /* upper bound on workgroups (grid-stride beyond it); 0 = one tile per workgroup */
   uint32_t launch_waves_per_cu; /* cap on resident wavefronts per compute unit, 2..32 (enforced by reserving LDS per

@@ -414,7 +414,44 @@ __device__ __forceinline__ void batch_updates(const GradSet& gs, const BatchPlan
   consume(g, w_cur);
 }
 
-template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int NTLD = kStateLoadsCached>
+// The same walk for SHORT vectors (a single generation of waves, so a launch lasts as many memory round trips as a wave
+// makes): R gradient loads per round, consumed in list order; the plan entry of the next update is fetched when an
+// update completes.  Same operations in the same order per element as batch_updates.
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int R, typename T>
+__device__ __forceinline__ void batch_updates_rounds(const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a, uint64_t i,
+                                                     T& th, T& ve, Norms& n) {
+  const uint32_t total = a.c;
+  Norms unused = {0.f, 0.f, 0.f, 0.f};
+  UpdateArgs au = a;
+  uint32_t u = 0, pos = 0;
+  BatchPlan::Entry cur = plan.e[0];
+  T s{};
+  auto consume = [&](T g, float w) {
+    if (WEIGHTED) g = g * w;
+    if (pos == 0) s = g;
+    else s = s + g;
+    if (++pos == cur.count) {
+      au.lr = cur.lr;
+      au.inv_c = cur.inv_c;
+      if (STATS && u + 1 == plan.n_updates) update_lane<OPT, DECAY, true>(s, th, ve, au, n);
+      else update_lane<OPT, DECAY, false>(s, th, ve, au, unused);
+      pos = 0;
+      ++u;
+      cur = plan.e[u < (uint32_t)kMaxBatchUpdates ? u : (uint32_t)kMaxBatchUpdates - 1];
+    }
+  };
+  uint32_t j = 0;
+  for (; j + R <= total; j += R) {
+    T g[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) g[k] = load_grad_global<T>(reinterpret_cast<uint64_t>(gs.p[j + k]), i);
+#pragma unroll
+    for (int k = 0; k < R; ++k) consume(g[k], gs.w[j + k]);
+  }
+  for (; j < total; ++j) consume(load_grad_global<T>(reinterpret_cast<uint64_t>(gs.p[j]), i), gs.w[j]);
+}
+
+template <int OPT, bool DECAY, bool WEIGHTED, bool STATS, int NTLD = kStateLoadsCached, int R = 1>
 __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan, const UpdateArgs a) {
   typedef floatx4 T;
   const uint64_t npos = a.n_params >> 2;
@@ -429,7 +466,8 @@ __global__ void apply_update_batch_kernel(const GradSet gs, const BatchPlan plan
     if (i >= npos) continue;
     T th = load_state4<NTLD == kStateLoadsThetaNt>(theta, i), ve{};
     if (OPT != kOptSgd) ve = load_state4<NTLD == kStateLoadsVelNt>(vel, i);
-    batch_updates<OPT, DECAY, WEIGHTED, STATS, T>(gs, plan, a, i, th, ve, n);
+    if (R > 1) batch_updates_rounds<OPT, DECAY, WEIGHTED, STATS, R, T>(gs, plan, a, i, th, ve, n);
+    else batch_updates<OPT, DECAY, WEIGHTED, STATS, T>(gs, plan, a, i, th, ve, n);
     __builtin_nontemporal_store(th, theta_out + i);
     if (OPT != kOptSgd) __builtin_nontemporal_store(ve, vel + i);
   }

@@ -82,6 +82,7 @@ constexpr int kNoAllocMaxDevices = 64;
 static_assert(sizeof(g_noalloc_scratch) == (size_t)kNoAllocSlots * kNumNorms * sizeof(double), "scratch array and slot count disagree");
 std::mutex g_noalloc_mu;
 double* g_noalloc_slots[kNoAllocMaxDevices] = {};  // per device: address of its copy of g_noalloc_scratch
+uint32_t g_noalloc_cus[kNoAllocMaxDevices] = {};   // per device: its compute units (looked up with the address)
 
 struct Pending {
   const float* ptr;
@@ -220,6 +221,23 @@ uint32_t grid_for(uint64_t tiles, uint32_t block, uint32_t cap) {
   return (uint32_t)grid;
 }
 
+// Gradient loads a wave issues per round when the caller names no unroll.  Up to kDefaultUnroll gradients: all at once.
+// More: one at a time (see default_waves_per_cu), except on short vectors.  A vector of fewer wavefront tiles than the
+// chip holds resident wavefronts (32 per CU) is a single generation of waves: nothing queues behind them, the launch
+// lasts about c / U memory round trips, and deeper rounds pay.  Measured in one process, c = 7 / 15 / 30, microseconds
+// per update: 131k parameters 4.9 / 8.1 / 14.1 at U = 1 -> 3.7 / 4.6 / 6.6 at U = 8; 400k: 6.5 / 10.4 / 17.6 -> 5.6 / 7.7 /
+// 11.5 at U = 4; 1.0M: 10.0 / 15.8 / 25.1 -> 10.4 / 14.9 / 23.1 at U = 2 (hence not for c <= 8); from 1.25M on U = 1 wins.
+uint32_t default_unroll(uint32_t c, uint64_t n_params, uint32_t n_cus, uint32_t vec) {
+  if (c <= kDefaultUnroll) return kDefaultUnroll;
+  const uint64_t waves = ((n_params >> 2) + 63) / 64;
+  const uint64_t resident = (uint64_t)n_cus * 32u;
+  uint32_t u = 1;
+  while (u < 8 && waves * (2u * u) <= resident) u *= 2;
+  if (u == 2 && c <= 8) u = 1;
+  while (u > 1 && u * vec > 8) u /= 2;
+  return u;
+}
+
 // Resident wavefronts per CU for the single-update kernel when the caller names none.
 // Measured at 72M parameters (GB/s of algorithmic bytes, medians): what counts is how many loads are in flight per
 // CU, about kInFlightKiBPerCu KiB at 1 KiB per wave-load, and, at equal volume, that few tiles are open at once.
@@ -236,9 +254,17 @@ uint32_t default_waves_per_cu(uint32_t c, uint32_t unroll, int optimizer, uint64
   const uint32_t waves_per_wg = block / 64;
   uint32_t w = (kInFlightKiBPerCu + per_wave / 2) / per_wave;
   if (c <= unroll) w = std::max(w, 16u);
-  else if (unroll == 1) w = n_params < kSmallVector ? 32 : 26;
+  else if (n_params < kSmallVector) w = 32;
+  else if (unroll == 1) w = 26;
   w = std::max(w, std::max(4u, waves_per_wg));
   return std::min(w, 32u);
+}
+
+void choose_unroll_and_waves(rudra_ps* ps) {
+  const rudra_ps_config_t& cfg = ps->cfg;
+  ps->unroll = cfg.launch_unroll ? cfg.launch_unroll : default_unroll(ps->c, cfg.n_params, ps->n_cus, ps->vec);
+  ps->waves_per_cu = cfg.launch_waves_per_cu ? cfg.launch_waves_per_cu
+                                             : default_waves_per_cu(ps->c, ps->unroll, kernel_optimizer(cfg), cfg.n_params, ps->block);
 }
 
 LaunchShape shape_for(const rudra_ps* ps) {
@@ -564,8 +590,12 @@ int enqueue_update(rudra_ps* ps, const Pending* g, size_t n_msgs, uint32_t count
 
 // ---- batched launches: several consecutive updates applied in registers (rudra_ps_push_batch) ----
 template <int OPT, bool WD, bool W, bool ST>
-void launch_batch_d(int ntld, LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
-  if (ntld == rudra::kStateLoadsThetaNt)
+void launch_batch_d(int ntld, uint32_t rounds, LaunchShape s, hipStream_t st, const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
+  if (rounds == 8)  // short vectors are cache-resident: no state-load policy there
+    hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsCached, 8>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  else if (rounds == 4)
+    hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsCached, 4>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
+  else if (ntld == rudra::kStateLoadsThetaNt)
     hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsThetaNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
   else if (ntld == rudra::kStateLoadsVelNt && OPT != rudra::kOptSgd)
     hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST, rudra::kStateLoadsVelNt>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
@@ -573,32 +603,42 @@ void launch_batch_d(int ntld, LaunchShape s, hipStream_t st, const GradSet& gs, 
     hipLaunchKernelGGL((rudra::apply_update_batch_kernel<OPT, WD, W, ST>), dim3(s.grid), dim3(s.block), s.lds_bytes, st, gs, plan, a);
 }
 template <int OPT, bool WD>
-void launch_batch_ws(bool weighted, bool stats, int ntld, LaunchShape s, hipStream_t st, const GradSet& gs,
+void launch_batch_ws(bool weighted, bool stats, int ntld, uint32_t rounds, LaunchShape s, hipStream_t st, const GradSet& gs,
                      const BatchPlan& plan, const UpdateArgs& a) {
   if (weighted) {
-    if (stats) launch_batch_d<OPT, WD, true, true>(ntld, s, st, gs, plan, a);
-    else launch_batch_d<OPT, WD, true, false>(ntld, s, st, gs, plan, a);
+    if (stats) launch_batch_d<OPT, WD, true, true>(ntld, rounds, s, st, gs, plan, a);
+    else launch_batch_d<OPT, WD, true, false>(ntld, rounds, s, st, gs, plan, a);
   } else {
-    if (stats) launch_batch_d<OPT, WD, false, true>(ntld, s, st, gs, plan, a);
-    else launch_batch_d<OPT, WD, false, false>(ntld, s, st, gs, plan, a);
+    if (stats) launch_batch_d<OPT, WD, false, true>(ntld, rounds, s, st, gs, plan, a);
+    else launch_batch_d<OPT, WD, false, false>(ntld, rounds, s, st, gs, plan, a);
   }
 }
-void launch_batch(int opt, bool decay, bool weighted, bool stats, int ntld, LaunchShape s, hipStream_t st,
+void launch_batch(int opt, bool decay, bool weighted, bool stats, int ntld, uint32_t rounds, LaunchShape s, hipStream_t st,
                   const GradSet& gs, const BatchPlan& plan, const UpdateArgs& a) {
   switch (opt) {
     case rudra::kOptMomentum:
-      if (decay) launch_batch_ws<rudra::kOptMomentum, true>(weighted, stats, ntld, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptMomentum, false>(weighted, stats, ntld, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptMomentum, true>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptMomentum, false>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
       break;
     case rudra::kOptAdagrad:
-      if (decay) launch_batch_ws<rudra::kOptAdagrad, true>(weighted, stats, ntld, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptAdagrad, false>(weighted, stats, ntld, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptAdagrad, true>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptAdagrad, false>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
       break;
     default:
-      if (decay) launch_batch_ws<rudra::kOptSgd, true>(weighted, stats, ntld, s, st, gs, plan, a);
-      else launch_batch_ws<rudra::kOptSgd, false>(weighted, stats, ntld, s, st, gs, plan, a);
+      if (decay) launch_batch_ws<rudra::kOptSgd, true>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
+      else launch_batch_ws<rudra::kOptSgd, false>(weighted, stats, ntld, rounds, s, st, gs, plan, a);
       break;
   }
+}
+
+// Gradient loads per round in a batched launch: 1 = the rolling scheme (gradient j consumed while j + 1 is in flight), which
+// is what long vectors want; short vectors (see default_unroll) take 8 or 4 at a time.  An explicit launch_unroll of 4
+// or 8 selects that; 1 or 2 the rolling scheme.
+uint32_t batch_rounds(const rudra_ps* ps) {
+  if (ps->cfg.launch_unroll) return ps->cfg.launch_unroll >= 4 ? ps->cfg.launch_unroll : 1u;
+  const uint64_t waves = ((ps->cfg.n_params >> 2) + 63) / 64;
+  const uint64_t resident = (uint64_t)ps->n_cus * 32u;
+  return waves * 8u <= resident ? 8u : waves * 4u <= resident ? 4u : 1u;
 }
 
 // Launch shape of a batched launch: one float4 per lane per tile whatever launch_vec says (theta and v stay in
@@ -637,7 +677,7 @@ int enqueue_batch(rudra_ps* ps, const Pending* g, const DeferredUpdate* d, uint3
   if (rc != RUDRA_OK) return rc;
   rc = begin_timed(ps, &slot);
   if (rc != RUDRA_OK) return rc;
-  launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, batch_state_load_policy(ps, n), s, ps->stream, gs, plan, a);
+  launch_batch(kernel_optimizer(ps->cfg), ps->cfg.weight_decay != 0.0f, weighted, ps->want_norms, batch_state_load_policy(ps, n), batch_rounds(ps), s, ps->stream, gs, plan, a);
   RUDRA_HIP(ps, hipGetLastError());
   rc = end_timed(ps, slot);
   if (rc != RUDRA_OK) return rc;
@@ -779,13 +819,10 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
   ps->stream = (hipStream_t)config->stream;
   ps->c = gradients_per_update(*config);
   if (config->launch_block) ps->block = config->launch_block;
-  if (config->launch_unroll) ps->unroll = config->launch_unroll;
-  else ps->unroll = ps->c > kDefaultUnroll ? 1u : kDefaultUnroll;  // many gradients: one load at a time per wave, more waves
   if (config->launch_vec) ps->vec = config->launch_vec;
   ps->grid_cap = config->launch_grid;
   ps->alternate = config->launch_alternate != 2;
-  ps->waves_per_cu = config->launch_waves_per_cu ? config->launch_waves_per_cu
-                                                 : default_waves_per_cu(ps->c, ps->unroll, kernel_optimizer(*config), config->n_params, ps->block);
+  choose_unroll_and_waves(ps);  // with the default CU count; again below once the device has been asked
   ps->ring = config->clock_ring ? config->clock_ring : kDefaultClockRing;
   try {
     ps->clock_cap = ps->c + (config->max_aggregate > 1 ? config->max_aggregate - 1 : 0);  // bounded by validate_config
@@ -813,6 +850,7 @@ int rudra_ps_create(const rudra_ps_config_t* config, const float* init_weights, 
       int cus = 0;
       if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, config->device) == hipSuccess && cus > 0) ps->n_cus = (uint32_t)cus;
       else (void)hipGetLastError();
+      choose_unroll_and_waves(ps);
     }
     if (e == hipSuccess) e = hipMalloc((void**)&ps->theta2[0], bytes);
     if (e == hipSuccess && ps->double_buffer) e = hipMalloc((void**)&ps->theta2[1], bytes);
@@ -1091,21 +1129,26 @@ int rudra_ps_apply_update_noalloc(const float* const* grads, uint32_t c, uint64_
   // The device address of this GPU's copy of the scratch array, looked up once per device with that device current.
   // In host code the array's name is only a handle for this lookup: kernels and copies take `slots`, never the name.
   double* slots = nullptr;
+  uint32_t n_cus = 256;
   {
     std::lock_guard<std::mutex> lock(g_noalloc_mu);
     if (!g_noalloc_slots[device]) {
       void* p = nullptr;
       if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return RUDRA_EHIP; }
+      int cus = 0;
+      if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0) { (void)hipGetLastError(); cus = 256; }
+      g_noalloc_cus[device] = (uint32_t)cus;
       g_noalloc_slots[device] = static_cast<double*>(p);
     }
     slots = g_noalloc_slots[device];
+    n_cus = g_noalloc_cus[device];
   }
 
   // one norm slot per tile of kNoAllocBlock float4 positions: no grid-stride, so the slot count is the tile count
   const uint64_t n4 = n_params >> 2;
   const uint64_t tiles = (n4 + kNoAllocBlock - 1) / kNoAllocBlock;
   const uint32_t grid = (uint32_t)(tiles ? tiles : 1);  // <= kNoAllocSlots by the size check above
-  const uint32_t unroll = c > kDefaultUnroll ? 1u : kDefaultUnroll;
+  const uint32_t unroll = default_unroll(c, n_params, n_cus, 1);
   const LaunchShape shape = {grid, kNoAllocBlock, tiles,
                              lds_for_occupancy(default_waves_per_cu(c, unroll, opt, n_params, kNoAllocBlock), kNoAllocBlock)};
   GradSet gs;

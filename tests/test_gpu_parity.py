@@ -567,6 +567,18 @@ def test_batched_pushes_give_the_bits_of_single_pushes(hipmod, name):
     hip.close()
 
 
+@pytest.mark.parametrize("unroll", [1, 4, 8])
+@pytest.mark.parametrize("name", ["c1-momentum-decay", "c7-stragglers", "adagrad", "per-gradient-weights",
+                                  "c33-two-updates-do-not-fit", "wide-c18-heavy-tail"])
+def test_batched_loads_per_round_give_the_same_bits(hipmod, name, unroll):
+    """A batched launch walks its gradient list one load ahead (long vectors) or 4 / 8 loads per round (the default for
+    short ones); launch_unroll names the scheme.  Lists whose length is no multiple of the round included."""
+    w, chunks = BATCH_CASES[name]
+    hip, ora = _run_both_batched(hipmod, w, chunks, launch_unroll=unroll)
+    _compare(hip, ora, w)
+    hip.close()
+
+
 @pytest.mark.parametrize("P", [1, 4, 5, 63, 64, 65, 257, 1024 + 3])
 def test_batched_pushes_on_ragged_vectors(hipmod, P):
     w = configs.C5.scaled(n_params=P, n_pushes=40)
