@@ -476,6 +476,16 @@ def main():
                            "weight_copies_per_update": rp["copies"] / rp["updates"], "HBM_GBps_updates_plus_copies": moved / rp["wall_s"] / 1e9,
                            "launches_made_to_wait_for_readers": rp["reader_waits"]}
         line["extra"]["C4-with-18-weight-pulls-per-update"] = pulls
+        # the short-vector workloads (131k and 1.0M parameters: cache-resident, one generation of waves per launch; read
+        # their applyUpdates/s and the time per launch, not a roofline fraction), singly and with 64 messages per call
+        short = {}
+        for key, k in (("C1", 1), ("C2", 1), ("C3-n1", 1), ("C3-n2", 1), ("C3-n4", 1), ("C3-n30", 1), ("C1", 64), ("C3-n30", 64)):
+            ws = configs.ALL[key]
+            rs = run_gpu(ws, 2048 if k > 1 else 2000, 64, ring=max(args.ring, k + ws.c + 1), flags=base_flags, batch=k, **launch)
+            short[ws.name + (f"-{k}-messages-per-call" if k > 1 else "")] = {
+                "applyUpdates_per_s": rs["updates"] / rs["wall_s"], "n_params": ws.n_params, "gradients_per_update": ws.c,
+                "avg_launch_us": 1e3 * rs["event_ms"] / rs["timed_launches"], "updates_per_launch": rs["updates"] / rs["timed_launches"]}
+        line["extra"]["short-vector-workloads"] = short
     if not args.no_cpu_baseline:
         cb = run_cpu_oracle(w)
         line["cpu_baseline"] = {"value": cb["value"], "unit": "applyUpdates/s", "cores": cb["cores"], "kind": "oracle",
