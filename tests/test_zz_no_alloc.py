@@ -69,6 +69,14 @@ def test_noalloc_update_equals_the_server_path_twice_in_a_row_the_second_smaller
     _case(B, 5, 2, 2, 0.05, 0.9, 0.0, B.OPT_SGD, 0.0, stream)                   # shorter than one float4: the scalar tail alone
 
 
+def test_noalloc_update_at_the_largest_vector_its_scratch_serves():
+    """P = 134 217 728: 131 072 tiles of 1024 parameters, one norm slot each, which is every slot of the fixed array."""
+    from paper_1509_04210_amd import binding as B
+    B.lib()
+    _case(B, 6, 134_217_728, 2, 0.05, 0.9, 5e-4, B.OPT_SGD, 0.0, torch.cuda.Stream())
+    torch.cuda.empty_cache()
+
+
 def test_noalloc_update_rejects_what_its_fixed_scratch_cannot_serve():
     from paper_1509_04210_amd import binding as B
     B.lib()
