@@ -346,3 +346,31 @@ def test_phased_kernel_is_not_used_with_fused_norms_or_by_default(hipmod):
         _compare(hip, ora, w)
         assert hip.ps.stats().n_phased_launches == want
         hip.close()
+
+
+# ---------------------------------------------------------------- a run that diverges: overflow, infinities and NaN
+def _same_bits_or_both_nan(a, b):
+    """Bit-identical wherever a number (an infinity included) stands; NaN where the other has NaN.  The sign and payload of a
+    NaN that an operation creates are the one thing IEEE 754 leaves to the machine, and the two machines differ there."""
+    a, b = np.ascontiguousarray(a, dtype=np.float32), np.ascontiguousarray(b, dtype=np.float32)
+    na, nb = np.isnan(a), np.isnan(b)
+    return np.array_equal(na, nb) and np.array_equal(a.view(np.uint32)[~na], b.view(np.uint32)[~nb])
+
+
+@pytest.mark.parametrize("optimizer,batched", [("sgd", False), ("adagrad", False), ("sgd", True)])
+def test_a_diverging_run_overflows_like_the_oracle(hipmod, optimizer, batched):
+    """Too large a rate on stale gradients makes training diverge (Sec. 5.1).  Here the numbers themselves run out
+    (weights of 1e37 and gradients of 7e37 overflow in the sum of an update, in the step and in the squared-gradient sums;
+    inf - inf and inf / inf then give NaN).  The kernel must produce
+    infinities and NaN exactly where the CPU does, and the same bits everywhere else."""
+    from tests.test_gpu_parity import _run_both, _run_both_batched
+    w = _with(configs.C3(2).scaled(n_params=30_003, n_pushes=15 * 4), init_std=1e37, grad_std=7e37, alpha0=0.75,
+              momentum=0.9 if optimizer == "sgd" else 0.0, weight_decay=0.0 if optimizer == "sgd" else 0.5, optimizer=optimizer,
+              adagrad_eps=0.0 if optimizer == "sgd" else 1e-8)
+    hip, ora = _run_both_batched(hipmod, w, [40, 15, 35]) if batched else _run_both(hipmod, w)
+    theta, state = ora.ps.theta, ora.ps.velocity
+    assert np.isnan(theta).mean() > 0.1 and np.isfinite(theta).mean() > 0.1                  # the case has all three kinds of
+    assert np.isinf(theta).mean() > 0.1 or np.isinf(state).mean() > 0.1                      # values, each in quantity
+    assert _same_bits_or_both_nan(hip.weights().cpu().numpy(), theta)
+    assert _same_bits_or_both_nan(hip.velocity().cpu().numpy(), state)
+    hip.close()
