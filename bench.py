@@ -170,10 +170,9 @@ def run_gpu_tree(w, fan_in, steps, warmup, ring=64):
 def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
     """A workload with the pullWeights traffic of its learners: after every applyUpdate each of the lambda learners fetches
     the new weights (a device copy of the vector each).  overlap = False: rudra_ps_pull_weights, i.e. the copies queue on
-    the server's stream between the updates.  overlap = True: two weight buffers (RUDRA_FLAG_DOUBLE_BUFFER), the copies run
-    on reader streams from the buffer rudra_ps_weights_acquire hands out, concurrently with the next update, and
-    rudra_ps_weights_release makes the update after that one wait for them (Sec. 3.3: computation and communication
-    buffers with a pointer swap)."""
+    the server's stream between the updates.  overlap = True: two weight buffers (RUDRA_FLAG_DOUBLE_BUFFER) and
+    rudra_ps_pull_weights_on: the copies run on reader streams, concurrently with the next update, and the update after
+    that one waits for them (Sec. 3.3: computation and communication buffers with a pointer swap)."""
     import torch
     from paper_1509_04210_amd import binding as B
     from synth.learners import HipServer
@@ -185,8 +184,6 @@ def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
     ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
     dsts = [torch.empty(P, dtype=torch.float32, device=hip.dev) for _ in range(4)]      # where the learners' copies land
     readers = [torch.cuda.Stream(device=hip.dev) for _ in range(n_reader_streams)]
-    rt = ctypes.CDLL("libamdhip64.so")
-    rt.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
     torch.cuda.synchronize()
     learner_ts = [0] * lam
     n_copies = 0
@@ -198,14 +195,9 @@ def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
                 ps.pull_weights(dsts[l % len(dsts)].data_ptr())
                 n_copies += 1
             return
-        for r, rs in enumerate(readers):
-            ptr, _, ticket = ps.weights_acquire(rs.cuda_stream)
-            for l in range(r, lam, len(readers)):
-                if rt.hipMemcpyAsync(dsts[l % len(dsts)].data_ptr(), ptr, 4 * P, 3, rs.cuda_stream) != 0:     # 3 = device to device
-                    raise RuntimeError("hipMemcpyAsync failed")
-                n_copies += 1
-            if ps.weights_release(ticket, rs.cuda_stream) != B.OK:
-                raise RuntimeError("weights_release came too late")
+        for l in range(lam):
+            ps.pull_weights_on(dsts[l % len(dsts)].data_ptr(), readers[l % len(readers)].cuda_stream)
+            n_copies += 1
 
     def run_range(lo, hi):
         for i in range(lo, hi):

@@ -241,8 +241,9 @@ int rudra_ps_push_aggregate(rudra_ps_t* ps, const float* avg, const uint64_t* ts
 int rudra_ps_leaf_mean(const float* const* grads, uint32_t k, uint64_t n_params, float* out, int32_t device, void* stream);
 
 /* pullWeights (Sec. 2, Sec. 3.2 "Learner"): the weights and their timestamp.  dst: DEVICE pointer to P floats
- * receiving a copy enqueued on the stream after all updates so far, or NULL for the timestamp inquiry a learner
- * makes first to skip the transfer.  ts_out: HOST pointer, may be NULL. */
+ * receiving a copy enqueued on the stream after all updates so far (the library's own copy kernel when dst is 16-byte
+ * aligned, else the runtime's device-to-device copy), or NULL for the timestamp inquiry a learner makes first to skip the
+ * transfer.  ts_out: HOST pointer, may be NULL. */
 int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out);
 
 /* Zero-copy pullWeights: a DEVICE pointer to the P weights of the current timestamp (HOST pointers theta_out, ts_out
@@ -269,6 +270,15 @@ int rudra_ps_weights_view(rudra_ps_t* ps, const float** theta_out, uint64_t* ts_
  * Errors: EINVAL, ESTATE (CONTROL_ONLY; release too late), ENOMEM, EHIP. */
 int rudra_ps_weights_acquire(rudra_ps_t* ps, void* reader_stream, const float** theta_out, uint64_t* ts_out, uint64_t* ticket_out);
 int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_stream);
+
+/* pullWeights on the READER's stream (Sec. 3.3: the learner's pull thread fetches the weights while the computation goes
+ * on): acquire, copy and release in one call.  reader_stream (hipStream_t of the same device, may be NULL = null stream)
+ * waits for the work that produces the current weights, the copy into dst (DEVICE pointer, P floats) runs there, and the
+ * applyUpdate launch that next writes the buffer the copy reads waits for it on the device: with
+ * RUDRA_FLAG_DOUBLE_BUFFER that is the second launch from now, so the copy overlaps the next update; without the flag it
+ * is the next launch.  No host call blocks.  Given the server's own stream it is rudra_ps_pull_weights.  Counted in
+ * n_weight_copies.  ts_out: HOST pointer, may be NULL.  Errors: EINVAL, ESTATE (CONTROL_ONLY), ENOMEM, EHIP. */
+int rudra_ps_pull_weights_on(rudra_ps_t* ps, float* dst, void* reader_stream, uint64_t* ts_out);
 
 /* The launch shape the next single-update launch (batched = 0) or batched launch (batched != 0) would use: workgroups,
  * threads per workgroup, tiles of the vector (more than the workgroups when the grid is capped: grid-stride), LDS

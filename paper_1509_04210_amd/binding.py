@@ -73,6 +73,7 @@ def lib():
             "rudra_ps_weights_view": [vp, C.POINTER(vp), C.POINTER(u64)],
             "rudra_ps_weights_acquire": [vp, vp, C.POINTER(vp), C.POINTER(u64), C.POINTER(u64)],
             "rudra_ps_weights_release": [vp, u64, vp],
+            "rudra_ps_pull_weights_on": [vp, vp, vp, C.POINTER(u64)],
             "rudra_ps_launch_shape": [vp, i32, C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(u32)],
             "rudra_ps_pull_velocity": [vp, vp],
             "rudra_ps_stats": [vp, C.POINTER(Stats)],
@@ -175,6 +176,14 @@ class ParameterServer:
         rc = self._L.rudra_ps_pull_weights(self._h, dst_ptr or None, C.byref(ts))
         if rc != OK:
             raise RudraError(rc, "rudra_ps_pull_weights")
+        return ts.value
+
+    def pull_weights_on(self, dst_ptr, reader_stream=0):
+        """Timestamp of the weights; the copy into dst_ptr runs on reader_stream, ordered against the server's launches."""
+        ts = C.c_uint64()
+        rc = self._L.rudra_ps_pull_weights_on(self._h, dst_ptr, reader_stream or None, C.byref(ts))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_pull_weights_on")
         return ts.value
 
     def weights_view(self):

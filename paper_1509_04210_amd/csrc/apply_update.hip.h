@@ -631,4 +631,24 @@ __global__ void sum_gradients_kernel(const GradSet gs, const UpdateArgs a) {
   }
 }
 
+// pullWeights (Sec. 2, Sec. 3.2): dst = src, P floats; 8 bytes per parameter, HBM-bound.  One float4 per lane, one
+// wavefront per workgroup as in the update kernels; the source with ordinary loads (every learner pulls the same
+// weights, and the update that follows reads them again), the destination (read by nobody on this side) with
+// non-temporal stores.  Measured at 72M parameters against the runtime's device-to-device copy in one process: 83 us
+// (6.9 TB/s read + written) vs 107 us (5.4 TB/s); non-temporal loads 86 us, ordinary stores 92 us, 256-thread
+// workgroups 88 us.  The P % 4 tail by the first lanes of workgroup 0.  Both pointers 16-byte aligned.
+__global__ void copy_vector_kernel(const float* __restrict__ src, float* __restrict__ dst, uint64_t n_params, uint64_t ntiles) {
+  const uint64_t n4 = n_params >> 2;
+  const floatx4* s4 = reinterpret_cast<const floatx4*>(src);
+  floatx4* d4 = reinterpret_cast<floatx4*>(dst);
+  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const uint64_t i = t * blockDim.x + threadIdx.x;
+    if (i < n4) __builtin_nontemporal_store(s4[i], d4 + i);
+  }
+  if (blockIdx.x == 0) {
+    const uint64_t k = (n4 << 2) + threadIdx.x;
+    if (k < n_params) dst[k] = src[k];
+  }
+}
+
 }  // namespace rudra

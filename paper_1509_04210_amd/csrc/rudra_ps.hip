@@ -1175,6 +1175,18 @@ int rudra_ps_apply_update_noalloc(const float* const* grads, uint32_t c, uint64_
   return RUDRA_OK;
 }
 
+namespace {
+// dst = src (n floats) on `st`: the library's copy kernel when dst allows 128-bit stores (src is a hipMalloc'ed vector of
+// the server: always aligned), else the runtime's copy.
+hipError_t copy_vector(const float* src, float* dst, uint64_t n, hipStream_t st) {
+  if (reinterpret_cast<uintptr_t>(dst) & 15u) return hipMemcpyAsync(dst, src, n * sizeof(float), hipMemcpyDeviceToDevice, st);
+  const uint64_t n4 = n >> 2;
+  const uint64_t tiles = std::max<uint64_t>(1, (n4 + kDefaultBlock - 1) / kDefaultBlock);
+  hipLaunchKernelGGL(rudra::copy_vector_kernel, dim3(grid_for(tiles, kDefaultBlock, 0)), dim3(kDefaultBlock), 0, st, src, dst, n, tiles);
+  return hipGetLastError();
+}
+}  // namespace
+
 int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out) {
   if (!ps) return RUDRA_EINVAL;
   std::lock_guard<std::mutex> lock(ps->mu);
@@ -1183,7 +1195,7 @@ int rudra_ps_pull_weights(rudra_ps_t* ps, float* dst, uint64_t* ts_out) {
     if (ps->failed) return RUDRA_EHIP;
     DeviceGuard guard(ps->cfg.device);
     RUDRA_HIP(ps, guard.error());
-    RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->theta2[ps->cur], ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+    RUDRA_HIP(ps, copy_vector(ps->theta2[ps->cur], dst, ps->cfg.n_params, ps->stream));
     ps->n_weight_copies += 1;
   } else {
     ps->n_ts_inquiries += 1;
@@ -1254,6 +1266,42 @@ int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_strea
   return RUDRA_OK;
 }
 
+int rudra_ps_pull_weights_on(rudra_ps_t* ps, float* dst, void* reader_stream, uint64_t* ts_out) {
+  if (!ps || !dst) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
+  const hipStream_t rs = (hipStream_t)reader_stream;
+  const uint32_t buf = ps->cur;
+  if (rs == ps->stream) {
+    RUDRA_HIP(ps, copy_vector(ps->theta2[buf], dst, ps->cfg.n_params, ps->stream));
+  } else {
+    // acquire, copy, release in one step: the reader's stream waits for the work that produces these weights, the copy
+    // runs there, and the launch that next writes this buffer waits for the copy (on the device)
+    hipEvent_t ready, done;
+    int rc = take_event(ps, &ready);
+    if (rc != RUDRA_OK) return rc;
+    hipError_t e = hipEventRecord(ready, ps->stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(rs, ready, 0);
+    ps->free_events.push_back(ready);
+    RUDRA_HIP(ps, e);
+    rc = take_event(ps, &done);
+    if (rc != RUDRA_OK) return rc;
+    e = copy_vector(ps->theta2[buf], dst, ps->cfg.n_params, rs);
+    if (e == hipSuccess) e = hipEventRecord(done, rs);
+    if (e != hipSuccess) {
+      ps->free_events.push_back(done);
+      return hip_fail(ps, e);
+    }
+    ps->reader_done[buf].push_back(done);  // room was reserved when the event was created
+  }
+  ps->n_weight_copies += 1;
+  if (ts_out) *ts_out = ps->ts_cur;
+  return RUDRA_OK;
+}
+
 int rudra_ps_launch_shape(rudra_ps_t* ps, int32_t batched, uint32_t* grid_out, uint32_t* block_out, uint64_t* ntiles_out,
                           uint32_t* lds_bytes_out) {
   if (!ps) return RUDRA_EINVAL;
@@ -1273,7 +1321,7 @@ int rudra_ps_pull_velocity(rudra_ps_t* ps, float* dst) {
   if (ps->failed) return RUDRA_EHIP;
   DeviceGuard guard(ps->cfg.device);
   RUDRA_HIP(ps, guard.error());
-  RUDRA_HIP(ps, hipMemcpyAsync(dst, ps->vel, ps->cfg.n_params * sizeof(float), hipMemcpyDeviceToDevice, ps->stream));
+  RUDRA_HIP(ps, copy_vector(ps->vel, dst, ps->cfg.n_params, ps->stream));
   return RUDRA_OK;
 }
 

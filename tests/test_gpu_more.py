@@ -248,6 +248,67 @@ def test_reader_stream_copies_one_timestamp_while_later_updates_are_enqueued(hip
     hip.close()
 
 
+@pytest.mark.parametrize("double_buffer", [True, False])
+def test_pull_on_a_reader_stream_while_later_updates_are_enqueued(hipmod, double_buffer):
+    """rudra_ps_pull_weights_on: after the updates 1, 2 and 4 a busy second stream is handed a pull (acquire, copy, release in
+    one call) and the host goes on enqueueing updates.  Each copy equals the oracle's theta of its timestamp bit for bit,
+    the final weights too, and the launches that overwrite a buffer a copy reads were made to wait for it."""
+    from paper_1509_04210_amd import binding as B
+    w = configs.C3(2).scaled(n_params=2_000_003, n_pushes=15 * 6)                 # c = 15, six updates
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, flags=B.FLAG_DOUBLE_BUFFER if double_buffer else 0, ring=15 * 6 + 1)
+    ora = OracleServer(w)
+    reader = torch.cuda.Stream()
+    big_a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")             # 1 GiB
+    big_b = torch.empty_like(big_a)
+    snapshots, wanted = {}, {}
+    torch.cuda.synchronize()
+    ts_l = [0] * w.n_learners
+    n_updates = 0
+    for i in range(len(learner)):
+        l, s = int(learner[i]), int(step[i])
+        _, _, applied = hip.push(l, s, ts_l[l])
+        ora.push(l, s, ts_l[l])
+        ts_l[l] = hip.pull_ts()
+        n_updates += applied
+        if applied and n_updates in (1, 2, 4):
+            _slow_work(reader, big_a, big_b, 20)                                  # the reader is busy for a while ...
+            snapshots[n_updates] = torch.zeros(w.n_params + 1, dtype=torch.float32, device="cuda")
+            dst = snapshots[n_updates].data_ptr() + (4 if n_updates == 4 else 0)  # the third pull into a misaligned buffer
+            assert hip.ps.pull_weights_on(dst, reader.cuda_stream) == n_updates == ora.ps.ts
+            wanted[n_updates] = (ora.ps.theta.copy(), 1 if n_updates == 4 else 0)
+    assert n_updates == 6
+    hip.ps.sync()
+    torch.cuda.synchronize()
+    for ts, (theta, off) in wanted.items():
+        assert np.array_equal(snapshots[ts].cpu().numpy()[off:off + w.n_params], theta), f"the pull at timestamp {ts} saw other weights"
+    assert np.array_equal(hip.weights().cpu().numpy(), ora.ps.theta)
+    st = hip.ps.stats()
+    assert st.n_reader_waits == 3 and st.n_weight_copies >= 3
+    hip.close()
+
+
+@pytest.mark.parametrize("P", [1, 3, 4, 5, 255, 256, 257, 100_003])
+def test_pull_copies_every_element_and_nothing_else(hipmod, P):
+    """rudra_ps_pull_weights / _pull_velocity through the library's copy kernel (aligned destination) and through the
+    runtime's copy (misaligned one): all P elements, and not one float beyond them."""
+    w = configs.C5.scaled(n_params=P, n_pushes=7)
+    learner, step = w.arrival_trace()
+    hip, ora = hipmod.HipServer(w), OracleServer(w)
+    replay.replay(hip, learner, step, w.n_learners)
+    replay.replay(ora, learner, step, w.n_learners)
+    for off in (0, 1):
+        for pull, want in ((hip.ps.pull_weights, ora.ps.theta), (hip.ps.pull_velocity, ora.ps.velocity)):
+            dst = torch.full((P + 9,), 7.0, dtype=torch.float32, device="cuda")
+            torch.cuda.synchronize()
+            pull(dst.data_ptr() + 4 * (4 + off))
+            hip.ps.sync()
+            got = dst.cpu().numpy()
+            assert np.array_equal(got[4 + off:4 + off + P], want)
+            assert np.all(got[:4 + off] == 7.0) and np.all(got[4 + off + P:] == 7.0)
+    hip.close()
+
+
 def _copy_from_address(dst, src_ptr, n, stream):
     """hipMemcpyAsync(dst, src_ptr, 4n bytes, device to device) on `stream`."""
     import ctypes
