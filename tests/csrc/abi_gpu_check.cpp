@@ -221,13 +221,21 @@ int main() {
     CHECK(rudra_ps_push_gradient(ps, one, 1, 0, &r) == RUDRA_OK && r.applied);
     CHECK(rudra_ps_push_gradient(ps, one, 2, 0, &r) == RUDRA_OK && r.applied);
     CHECK(rudra_ps_weights_release(ps, ticket, reader) == RUDRA_ESTATE);   // the overwriting launch is enqueued: too late now
+    // the same in one call: the weights of timestamp 3 (1/4) pulled on the reader's stream, then two more updates
+    float* pulled = device_constant(0.0f);
+    CHECK(pulled && rudra_ps_pull_weights_on(ps, pulled, reader, &ts) == RUDRA_OK && ts == 3);
+    CHECK(rudra_ps_push_gradient(ps, one, 3, 0, &r) == RUDRA_OK && r.applied);
+    CHECK(rudra_ps_push_gradient(ps, one, 4, 0, &r) == RUDRA_OK && r.applied);
     CHECK(hipStreamSynchronize(reader) == hipSuccess && rudra_ps_sync(ps) == RUDRA_OK);
     std::vector<float> hc(P);
     CHECK(hipMemcpy(hc.data(), copy, P * sizeof(float), hipMemcpyDeviceToHost) == hipSuccess);
     for (uint64_t k = 0; k < P; ++k) CHECK(hc[k] == 0.75f);
-    CHECK(all_equal(ps, scratch, 0.25f));
+    CHECK(hipMemcpy(hc.data(), pulled, P * sizeof(float), hipMemcpyDeviceToHost) == hipSuccess);
+    for (uint64_t k = 0; k < P; ++k) CHECK(hc[k] == 0.25f);
+    CHECK(all_equal(ps, scratch, -0.25f));
     rudra_ps_stats_t st;
-    CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK && st.n_weight_acquires == 1 && st.n_reader_waits == 1);
+    CHECK(rudra_ps_stats(ps, &st) == RUDRA_OK && st.n_weight_acquires == 1 && st.n_reader_waits == 2);
+    (void)hipFree(pulled);
     CHECK(rudra_ps_destroy(ps) == RUDRA_OK);
     (void)hipFree(copy);
     (void)hipStreamDestroy(server); (void)hipStreamDestroy(reader);

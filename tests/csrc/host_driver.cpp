@@ -133,6 +133,10 @@ int main() {
     const float* p = nullptr; uint64_t ticket = 0;
     CHECK(rudra_ps_weights_acquire(ps, nullptr, &p, nullptr, &ticket) == RUDRA_ESTATE);
     CHECK(rudra_ps_weights_release(ps, 0, nullptr) == RUDRA_ESTATE);
+    float target[4];
+    CHECK(rudra_ps_pull_weights_on(ps, target, nullptr, nullptr) == RUDRA_ESTATE);
+    CHECK(rudra_ps_pull_weights_on(ps, nullptr, nullptr, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_pull_weights_on(nullptr, target, nullptr, nullptr) == RUDRA_EINVAL);
     float f;
     CHECK(rudra_ps_pull_velocity(ps, &f) == RUDRA_ESTATE);
     uint32_t grid = 0, block = 0, lds = 0; uint64_t tiles = 0;
