@@ -87,7 +87,9 @@ enum : int { kStateLoadsCached = 0, kStateLoadsVelNt = 1, kStateLoadsThetaNt = 2
 // volume, that few tiles are open at once (more concurrently open tiles keep more DRAM pages open and lose 3-6 %).
 // Measured optimum: c <= 4: all loads of a wave in one round, 16 waves; c > 4: ONE gradient load at a time per wave
 // (U = 1) and 26 waves.  Keeping 2-4 gradient loads rolling per wave, lanes that own 2-4 tiles (adjacent or strided),
-// per-XCD contiguous regions and grid-stride persistence were all measured and are slower or equal.
+// per-XCD contiguous regions and grid-stride persistence were all measured and are slower or equal.  Short vectors are
+// the exception: fewer tiles than the chip holds resident waves means one generation of waves and a launch that lasts
+// c / U memory round trips, so the host picks U = 2, 4 or 8 there (default_unroll in the host code, with the figures).
 __device__ __forceinline__ floatx4 load_grad4(const float* p, uint64_t iv) {
   return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p) + iv);
 }
