@@ -14,7 +14,6 @@ times (default 3) back to back; the headline is the median window.  Prints ONE J
 from __future__ import annotations
 
 import argparse
-import ctypes
 import json
 import os
 import statistics
