@@ -486,6 +486,13 @@ def main():
                                           f"(bit-identical to the single-thread run, which took {cb['single_seconds']:.1f} s)",
                                 "GBps": cb["value"] * bytes_upd / 1e9,
                                 "single_thread": {"value": cb["single_value"], "cores": 1, "GBps": cb["single_value"] * bytes_upd / 1e9}}
+        if args.workload == "C4" and plain and not args.no_extra:      # the other 72M workload beside it: 120 single-gradient updates
+            c5 = run_cpu_oracle(configs.C5, n_updates=120)
+            b5 = algorithmic_bytes_per_update(configs.C5)
+            line["cpu_baseline"]["other_workloads"] = {configs.C5.name: {
+                "value": c5["value"], "unit": "applyUpdates/s", "cores": c5["cores"], "GBps": c5["value"] * b5 / 1e9,
+                "sample": f"{c5['updates']} applyUpdates of one gradient each on the full vector, {c5['seconds']:.1f} s; single thread {c5['single_seconds']:.1f} s",
+                "single_thread": {"value": c5["single_value"], "cores": 1, "GBps": c5["single_value"] * b5 / 1e9}}}
     print(json.dumps(line))
 
 
