@@ -166,12 +166,14 @@ def run_gpu_tree(w, fan_in, steps, warmup, ring=64):
     return dict(wall_s=wall, event_ms=ev_ms, updates=steps, pushes=steps * w.c)
 
 
-def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
+def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2, broadcast=False):
     """A workload with the pullWeights traffic of its learners: after every applyUpdate each of the lambda learners fetches
     the new weights (a device copy of the vector each).  overlap = False: rudra_ps_pull_weights, i.e. the copies queue on
     the server's stream between the updates.  overlap = True: two weight buffers (RUDRA_FLAG_DOUBLE_BUFFER) and
     rudra_ps_pull_weights_on: the copies run on reader streams, concurrently with the next update, and the update after
-    that one waits for them (Sec. 3.3: computation and communication buffers with a pointer swap)."""
+    that one waits for them (Sec. 3.3: computation and communication buffers with a pointer swap).  broadcast = True: the
+    lambda copies of one update go out as ONE rudra_ps_broadcast_weights launch (weights read once, written lambda times),
+    on the server's stream or, with overlap, on a reader stream."""
     import torch
     from paper_1509_04210_amd import binding as B
     from synth.learners import HipServer
@@ -181,7 +183,7 @@ def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
     learner = [int(x) for x in learner]
     hip = HipServer(w, flags=B.FLAG_DOUBLE_BUFFER if overlap else 0, pregenerated=max(ring, c + 1))
     ps, bufs = hip.ps, [b.data_ptr() for b in hip.ring]
-    dsts = [torch.empty(P, dtype=torch.float32, device=hip.dev) for _ in range(4)]      # where the learners' copies land
+    dsts = [torch.empty(P, dtype=torch.float32, device=hip.dev) for _ in range(lam if broadcast else 4)]      # where the learners' copies land
     readers = [torch.cuda.Stream(device=hip.dev) for _ in range(n_reader_streams)]
     torch.cuda.synchronize()
     learner_ts = [0] * lam
@@ -189,6 +191,10 @@ def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2):
 
     def all_learners_pull():
         nonlocal n_copies
+        if broadcast:
+            ps.broadcast_weights([d.data_ptr() for d in dsts], readers[0].cuda_stream if overlap else hip.sh)
+            n_copies += lam
+            return
         if not overlap:
             for l in range(lam):
                 ps.pull_weights(dsts[l % len(dsts)].data_ptr())
@@ -460,9 +466,10 @@ def main():
         # C4 with its learners' pullWeights traffic (18 copies of the weights per update): queued on the server's stream,
         # or overlapped with the next update from the second weight buffer (Sec. 3.3)
         pulls = {}
-        for name, overlap in (("serialized_on_the_server_stream", False), ("overlapped_from_the_second_buffer", True)):
-            rp = run_gpu_pulls(configs.C4, 40, 4, overlap)
-            moved = rp["updates"] * algorithmic_bytes_per_update(configs.C4) + rp["copies"] * 8 * configs.C4.n_params
+        for name, overlap, bc in (("serialized_on_the_server_stream", False, False), ("overlapped_from_the_second_buffer", True, False),
+                                  ("one_broadcast_launch_on_the_server_stream", False, True), ("one_broadcast_launch_overlapped", True, True)):
+            rp = run_gpu_pulls(configs.C4, 40, 4, overlap, broadcast=bc)
+            moved = rp["updates"] * algorithmic_bytes_per_update(configs.C4) + (rp["copies"] * 4 + (rp["updates"] * 4 if bc else rp["copies"] * 4)) * configs.C4.n_params
             pulls[name] = {"applyUpdates_per_s": rp["updates"] / rp["wall_s"], "ms_per_update": 1e3 * rp["wall_s"] / rp["updates"],
                            "weight_copies_per_update": rp["copies"] / rp["updates"], "HBM_GBps_updates_plus_copies": moved / rp["wall_s"] / 1e9,
                            "launches_made_to_wait_for_readers": rp["reader_waits"]}

@@ -280,6 +280,15 @@ int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_strea
  * n_weight_copies.  ts_out: HOST pointer, may be NULL.  Errors: EINVAL, ESTATE (CONTROL_ONLY), ENOMEM, EHIP. */
 int rudra_ps_pull_weights_on(rudra_ps_t* ps, float* dst, void* reader_stream, uint64_t* ts_out);
 
+/* pullWeights for k learners at once: the broadcast of the new weights that ends a hardsync step (Sec. 3.1: every learner
+ * gets the updated weights before the next step) and the weight broadcast of Rudra-adv* (Sec. 3.3).  One launch reads the
+ * weights once and writes the k copies, P * (4 + 4k) bytes instead of the P * 8k of k pulls (more than 64 destinations go
+ * out as several launches).  dsts: HOST array of k DEVICE pointers (P floats each, 16-byte aligned, distinct, not
+ * overlapping).  Stream and ordering exactly as rudra_ps_pull_weights_on (give the server's own stream to queue it
+ * between the updates).  Counted as k weight copies.  ts_out: HOST pointer, may be NULL.
+ * Errors: EINVAL (null or misaligned destination, k = 0), ESTATE (CONTROL_ONLY), ENOMEM, EHIP. */
+int rudra_ps_broadcast_weights(rudra_ps_t* ps, float* const* dsts, uint32_t k, void* reader_stream, uint64_t* ts_out);
+
 /* The launch shape the next single-update launch (batched = 0) or batched launch (batched != 0) would use: workgroups,
  * threads per workgroup, tiles of the vector (more than the workgroups when the grid is capped: grid-stride), LDS
  * bytes reserved per workgroup as the occupancy cap.  Pure host arithmetic (works in CONTROL_ONLY mode): grid * block

@@ -74,6 +74,7 @@ def lib():
             "rudra_ps_weights_acquire": [vp, vp, C.POINTER(vp), C.POINTER(u64), C.POINTER(u64)],
             "rudra_ps_weights_release": [vp, u64, vp],
             "rudra_ps_pull_weights_on": [vp, vp, vp, C.POINTER(u64)],
+            "rudra_ps_broadcast_weights": [vp, C.POINTER(vp), u32, vp, C.POINTER(u64)],
             "rudra_ps_launch_shape": [vp, i32, C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(u32)],
             "rudra_ps_pull_velocity": [vp, vp],
             "rudra_ps_stats": [vp, C.POINTER(Stats)],
@@ -184,6 +185,16 @@ class ParameterServer:
         rc = self._L.rudra_ps_pull_weights_on(self._h, dst_ptr, reader_stream or None, C.byref(ts))
         if rc != OK:
             raise RudraError(rc, "rudra_ps_pull_weights_on")
+        return ts.value
+
+    def broadcast_weights(self, dst_ptrs, reader_stream=0):
+        """Timestamp of the weights; one launch on reader_stream writes them to every address in dst_ptrs."""
+        k = len(dst_ptrs)
+        arr = (C.c_void_p * k)(*dst_ptrs)
+        ts = C.c_uint64()
+        rc = self._L.rudra_ps_broadcast_weights(self._h, arr, k, reader_stream or None, C.byref(ts))
+        if rc != OK:
+            raise RudraError(rc, "rudra_ps_broadcast_weights")
         return ts.value
 
     def weights_view(self):

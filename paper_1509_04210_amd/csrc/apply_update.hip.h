@@ -653,4 +653,28 @@ __global__ void copy_vector_kernel(const float* __restrict__ src, float* __restr
   }
 }
 
+// pullWeights for k learners at once (the broadcast of new weights that ends a hardsync step, Sec. 3.1; the weight
+// broadcast of Rudra-adv*, Sec. 3.3): every lane reads its float4 of the weights ONCE and writes it to the k
+// destinations, P * (4 + 4k) bytes instead of the P * 8k of k copies.  Destination pointers come by value in the
+// kernarg (GradSet reused as a plain pointer list; the weights w[] are not read).  Same tiling and tail as
+// copy_vector_kernel; all pointers 16-byte aligned.
+__global__ void broadcast_vector_kernel(const float* __restrict__ src, const GradSet dsts, uint32_t k, uint64_t n_params, uint64_t ntiles) {
+  const uint64_t n4 = n_params >> 2;
+  const floatx4* s4 = reinterpret_cast<const floatx4*>(src);
+  for (uint64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const uint64_t i = t * blockDim.x + threadIdx.x;
+    if (i >= n4) continue;
+    const floatx4 x = s4[i];
+    for (uint32_t j = 0; j < k; ++j)
+      __builtin_nontemporal_store(x, reinterpret_cast<floatx4*>(const_cast<float*>(dsts.p[j])) + i);
+  }
+  if (blockIdx.x == 0) {
+    const uint64_t e = (n4 << 2) + threadIdx.x;
+    if (e < n_params) {
+      const float x = src[e];
+      for (uint32_t j = 0; j < k; ++j) const_cast<float*>(dsts.p[j])[e] = x;
+    }
+  }
+}
+
 }  // namespace rudra

@@ -1266,6 +1266,40 @@ int rudra_ps_weights_release(rudra_ps_t* ps, uint64_t ticket, void* reader_strea
   return RUDRA_OK;
 }
 
+extern "C++" {
+namespace {
+// Work that reads the current weights, enqueued on the reader's stream `rs` and ordered against the server's launches:
+// rs waits for the work that produces the weights, `enqueue(buffer, rs)` puts the reads there, and the applyUpdate launch
+// that next writes that buffer waits for them on the device.  On the server's own stream plain stream order does it.
+// Caller holds the mutex and has made the device current.
+template <typename Enqueue>
+int read_weights_on(rudra_ps* ps, hipStream_t rs, Enqueue enqueue) {
+  const uint32_t buf = ps->cur;
+  if (rs == ps->stream) {
+    RUDRA_HIP(ps, enqueue(ps->theta2[buf], rs));
+    return RUDRA_OK;
+  }
+  hipEvent_t ready, done;
+  int rc = take_event(ps, &ready);
+  if (rc != RUDRA_OK) return rc;
+  hipError_t e = hipEventRecord(ready, ps->stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent(rs, ready, 0);
+  ps->free_events.push_back(ready);
+  RUDRA_HIP(ps, e);
+  rc = take_event(ps, &done);
+  if (rc != RUDRA_OK) return rc;
+  e = enqueue(ps->theta2[buf], rs);
+  if (e == hipSuccess) e = hipEventRecord(done, rs);
+  if (e != hipSuccess) {
+    ps->free_events.push_back(done);
+    return hip_fail(ps, e);
+  }
+  ps->reader_done[buf].push_back(done);  // room was reserved when the event was created
+  return RUDRA_OK;
+}
+}  // namespace
+}  // extern "C++"
+
 int rudra_ps_pull_weights_on(rudra_ps_t* ps, float* dst, void* reader_stream, uint64_t* ts_out) {
   if (!ps || !dst) return RUDRA_EINVAL;
   std::lock_guard<std::mutex> lock(ps->mu);
@@ -1273,31 +1307,40 @@ int rudra_ps_pull_weights_on(rudra_ps_t* ps, float* dst, void* reader_stream, ui
   if (ps->failed) return RUDRA_EHIP;
   DeviceGuard guard(ps->cfg.device);
   RUDRA_HIP(ps, guard.error());
-  const hipStream_t rs = (hipStream_t)reader_stream;
-  const uint32_t buf = ps->cur;
-  if (rs == ps->stream) {
-    RUDRA_HIP(ps, copy_vector(ps->theta2[buf], dst, ps->cfg.n_params, ps->stream));
-  } else {
-    // acquire, copy, release in one step: the reader's stream waits for the work that produces these weights, the copy
-    // runs there, and the launch that next writes this buffer waits for the copy (on the device)
-    hipEvent_t ready, done;
-    int rc = take_event(ps, &ready);
-    if (rc != RUDRA_OK) return rc;
-    hipError_t e = hipEventRecord(ready, ps->stream);
-    if (e == hipSuccess) e = hipStreamWaitEvent(rs, ready, 0);
-    ps->free_events.push_back(ready);
-    RUDRA_HIP(ps, e);
-    rc = take_event(ps, &done);
-    if (rc != RUDRA_OK) return rc;
-    e = copy_vector(ps->theta2[buf], dst, ps->cfg.n_params, rs);
-    if (e == hipSuccess) e = hipEventRecord(done, rs);
-    if (e != hipSuccess) {
-      ps->free_events.push_back(done);
-      return hip_fail(ps, e);
-    }
-    ps->reader_done[buf].push_back(done);  // room was reserved when the event was created
-  }
+  const uint64_t n = ps->cfg.n_params;
+  int rc = read_weights_on(ps, (hipStream_t)reader_stream, [&](const float* theta, hipStream_t st) { return copy_vector(theta, dst, n, st); });
+  if (rc != RUDRA_OK) return rc;
   ps->n_weight_copies += 1;
+  if (ts_out) *ts_out = ps->ts_cur;
+  return RUDRA_OK;
+}
+
+int rudra_ps_broadcast_weights(rudra_ps_t* ps, float* const* dsts, uint32_t k, void* reader_stream, uint64_t* ts_out) {
+  if (!ps || !dsts || k == 0) return RUDRA_EINVAL;
+  for (uint32_t j = 0; j < k; ++j)
+    if (!dsts[j] || (reinterpret_cast<uintptr_t>(dsts[j]) & 15u)) return RUDRA_EINVAL;
+  std::lock_guard<std::mutex> lock(ps->mu);
+  if (ps->control_only) return RUDRA_ESTATE;
+  if (ps->failed) return RUDRA_EHIP;
+  DeviceGuard guard(ps->cfg.device);
+  RUDRA_HIP(ps, guard.error());
+  const uint64_t n = ps->cfg.n_params;
+  const uint64_t tiles = std::max<uint64_t>(1, ((n >> 2) + kDefaultBlock - 1) / kDefaultBlock);
+  const uint32_t grid = grid_for(tiles, kDefaultBlock, 0);
+  int rc = read_weights_on(ps, (hipStream_t)reader_stream, [&](const float* theta, hipStream_t st) {
+    for (uint32_t first = 0; first < k; first += (uint32_t)kMaxFused) {  // at most kMaxFused destinations per launch
+      const uint32_t m = std::min<uint32_t>(k - first, (uint32_t)kMaxFused);
+      GradSet set;
+      std::memset(&set, 0, sizeof(set));
+      for (uint32_t j = 0; j < m; ++j) set.p[j] = dsts[first + j];
+      hipLaunchKernelGGL(rudra::broadcast_vector_kernel, dim3(grid), dim3(kDefaultBlock), 0, st, theta, set, m, n, tiles);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  });
+  if (rc != RUDRA_OK) return rc;
+  ps->n_weight_copies += k;
   if (ts_out) *ts_out = ps->ts_cur;
   return RUDRA_OK;
 }

@@ -137,6 +137,13 @@ int main() {
     CHECK(rudra_ps_pull_weights_on(ps, target, nullptr, nullptr) == RUDRA_ESTATE);
     CHECK(rudra_ps_pull_weights_on(ps, nullptr, nullptr, nullptr) == RUDRA_EINVAL);
     CHECK(rudra_ps_pull_weights_on(nullptr, target, nullptr, nullptr) == RUDRA_EINVAL);
+    alignas(16) float aligned[4];
+    float* const dsts[1] = {aligned};
+    float* const odd[1] = {aligned + 1};
+    CHECK(rudra_ps_broadcast_weights(ps, dsts, 1, nullptr, nullptr) == RUDRA_ESTATE);
+    CHECK(rudra_ps_broadcast_weights(ps, odd, 1, nullptr, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_broadcast_weights(ps, dsts, 0, nullptr, nullptr) == RUDRA_EINVAL);
+    CHECK(rudra_ps_broadcast_weights(ps, nullptr, 1, nullptr, nullptr) == RUDRA_EINVAL);
     float f;
     CHECK(rudra_ps_pull_velocity(ps, &f) == RUDRA_ESTATE);
     uint32_t grid = 0, block = 0, lds = 0; uint64_t tiles = 0;

@@ -288,6 +288,46 @@ def test_pull_on_a_reader_stream_while_later_updates_are_enqueued(hipmod, double
     hip.close()
 
 
+@pytest.mark.parametrize("P,k,own_stream", [(1, 1, False), (5, 3, True), (257, 2, False), (100_003, 18, True), (70_001, 70, False), (2_000_003, 5, True)])
+def test_broadcast_writes_the_weights_of_one_timestamp_to_every_learner(hipmod, P, k, own_stream):
+    """rudra_ps_broadcast_weights: one launch (two beyond 64 destinations) reads the weights once and writes k copies, on
+    the server's stream or on a reader's; further updates are enqueued behind it.  Every copy equals the oracle's theta of
+    that timestamp, nothing is written beyond a copy's P floats, and the final weights are the oracle's."""
+    from paper_1509_04210_amd import binding as B
+    w = configs.C5.scaled(n_params=P, n_pushes=9)                                # c = 1: nine updates
+    learner, step = w.arrival_trace()
+    hip = hipmod.HipServer(w, flags=B.FLAG_DOUBLE_BUFFER if own_stream else 0)
+    ora = OracleServer(w)
+    reader = torch.cuda.Stream()
+    pad = 8
+    dsts = [torch.full((P + 2 * pad,), 7.0, dtype=torch.float32, device="cuda") for _ in range(k)]
+    torch.cuda.synchronize()
+    ts_l = [0] * w.n_learners
+    want = None
+    for i in range(len(learner)):
+        l, s = int(learner[i]), int(step[i])
+        hip.push(l, s, ts_l[l])
+        ora.push(l, s, ts_l[l])
+        ts_l[l] = hip.pull_ts()
+        if i == 3:
+            ts = hip.ps.broadcast_weights([d.data_ptr() + 4 * pad for d in dsts], reader.cuda_stream if own_stream else hip.stream.cuda_stream)
+            assert ts == 4 == ora.ps.ts
+            want = ora.ps.theta.copy()
+    hip.ps.sync()
+    torch.cuda.synchronize()
+    for d in dsts:
+        got = d.cpu().numpy()
+        assert np.array_equal(got[pad:pad + P], want)
+        assert np.all(got[:pad] == 7.0) and np.all(got[pad + P:] == 7.0)
+    assert np.array_equal(hip.weights().cpu().numpy(), ora.ps.theta)
+    st = hip.ps.stats()
+    assert st.n_weight_copies == k + 1 and st.n_reader_waits == (1 if own_stream else 0)
+    with pytest.raises(B.RudraError) as e:
+        hip.ps.broadcast_weights([dsts[0].data_ptr() + 4], 0)                    # a misaligned destination
+    assert e.value.status == B.EINVAL
+    hip.close()
+
+
 @pytest.mark.parametrize("P", [1, 3, 4, 5, 255, 256, 257, 100_003])
 def test_pull_copies_every_element_and_nothing_else(hipmod, P):
     """rudra_ps_pull_weights / _pull_velocity through the library's copy kernel (aligned destination) and through the
