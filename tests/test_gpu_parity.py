@@ -718,6 +718,37 @@ def test_random_configurations(hipmod, seed):
     hip.close()
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configurations_up_to_a_few_generations_of_waves(hipmod, seed):
+    """The same draw over vector lengths from below one tile to 2.2M parameters, where the library picks 8, 4, 2 or 1
+    gradient loads per round by itself (and 8, 4 or one-ahead in batched launches), or is told to."""
+    from paper_1509_04210_amd import binding as B
+    rng = np.random.default_rng(77000 + seed)
+    lam = int(rng.integers(1, 41))
+    hard = bool(rng.integers(0, 4) == 0)
+    n_split = 1 if hard else int(rng.integers(1, lam + 1))
+    optimizer = "adagrad" if rng.integers(0, 4) == 0 else "sgd"
+    momentum = 0.0 if optimizer == "adagrad" or rng.integers(0, 2) == 0 else float(rng.choice([0.5, 0.9, 0.99]))
+    lr_mode = str(rng.choice(["const", "static_n", "avg_staleness", "per_gradient"]))
+    base = configs.C2 if hard else configs.C3(1)
+    P = int(rng.choice([2, 5, 257, 4097, 65_537, 131_075, 262_147, 300_001, 524_293, 700_001, 1_048_579, 1_300_003, 2_200_001]))
+    w = _with(base, name=f"random-short-{seed}", n_params=P, n_learners=lam, n_split=n_split, protocol="hardsync" if hard else "softsync",
+              lr_mode=lr_mode, momentum=momentum, weight_decay=float(rng.choice([0.0, 5e-4])), optimizer=optimizer,
+              adagrad_eps=float(rng.choice([1e-8, 1e-3])), alpha0=float(rng.choice([0.001, 0.01, 0.1])),
+              n_pushes=int(rng.integers(1, 4)) * lam + int(rng.integers(0, lam)), tail_per=int(rng.choice([0, 100])),
+              straggler_prob=float(rng.choice([0.0, 0.2])), seed=int(rng.integers(1, 1 << 30)))
+    flags = int(rng.choice([0, 0, 0, B.FLAG_DOUBLE_BUFFER, B.FLAG_PUSH_ACCUMULATE, B.FLAG_STATS_NORMS]))
+    launch = dict(launch_unroll=int(rng.choice([0, 0, 0, 1, 2, 4, 8])), launch_waves_per_cu=int(rng.choice([0, 0, 13, 32])),
+                  launch_alternate=int(rng.choice([0, 1, 2])))
+    if rng.integers(0, 2):
+        chunks = [int(x) for x in rng.integers(1, 3 * w.c + 2, size=5)]
+        hip, ora = _run_both_batched(hipmod, w, chunks, flags=flags, **launch)
+    else:
+        hip, ora = _run_both(hipmod, w, flags=flags, **launch)
+    _compare(hip, ora, w)
+    hip.close()
+
+
 # ---------------------------------------------------------------- bench.py keeps its contract
 def test_bench_prints_one_json_line_with_the_agreed_fields(hipmod):
     import json
