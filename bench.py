@@ -213,6 +213,8 @@ def run_gpu_pulls(w, steps, warmup, overlap, ring=64, n_reader_streams=2, broadc
             learner_ts[l] = res.ts_after
             if res.applied:
                 all_learners_pull()
+                if w.protocol == "hardsync":       # the barrier: every learner starts the next step from the new weights
+                    learner_ts[:] = [res.ts_after] * lam
 
     run_range(0, warmup * c)
     ps.sync()
@@ -483,6 +485,12 @@ def main():
             short[ws.name + (f"-{k}-messages-per-call" if k > 1 else "")] = {
                 "applyUpdates_per_s": rs["updates"] / rs["wall_s"], "n_params": ws.n_params, "gradients_per_update": ws.c,
                 "avg_launch_us": 1e3 * rs["event_ms"] / rs["timed_launches"], "updates_per_launch": rs["updates"] / rs["timed_launches"]}
+        # hardsync ends every step with all learners fetching the new weights (Sec. 3.1): C2 with 30 pulls per update, and
+        # with the one broadcast launch instead
+        for name, bc in (("C2-with-30-weight-pulls-per-update", False), ("C2-with-one-broadcast-launch-per-update", True)):
+            rp = run_gpu_pulls(configs.C2, 1000, 50, False, broadcast=bc)
+            short[name] = {"applyUpdates_per_s": rp["updates"] / rp["wall_s"], "us_per_update": 1e6 * rp["wall_s"] / rp["updates"],
+                           "weight_copies_per_update": rp["copies"] / rp["updates"]}
         line["extra"]["short-vector-workloads"] = short
     if not args.no_cpu_baseline:
         cb = run_cpu_oracle(w)
