@@ -167,7 +167,8 @@ typedef struct {
   int32_t norms_valid;
   int32_t last_hip_error;   /* hipError_t of the latest failed HIP call, 0 if none */
   uint32_t reserved;
-  uint64_t n_weight_copies; /* rudra_ps_pull_weights calls that copied the weights ... */
+  uint64_t n_weight_copies; /* copies of the weights handed out: rudra_ps_pull_weights / _pull_weights_on calls that copied,
+                               k per rudra_ps_broadcast_weights ... */
   uint64_t n_ts_inquiries;  /* ... and those that only asked for the timestamp (Sec. 3.2 "Learner": a learner asks first
                                and skips the transfer when nothing changed) */
   uint64_t n_weight_views;  /* rudra_ps_weights_view calls */
